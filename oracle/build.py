@@ -1,0 +1,28 @@
+"""Compile the reference codec (oracle/zc_ref.c) into oracle/libzc_ref.so.
+
+Test infrastructure: the product library never links or loads this.
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "zc_ref.c")
+LIB = os.path.join(HERE, "libzc_ref.so")
+
+# -fwrapv: 32-bit wrap-around is part of the format definition.
+# -ffp-contract=off / no fast-math: every fp32 operation rounds once, as written.
+CFLAGS = ["-O2", "-std=c11", "-fwrapv", "-ffp-contract=off", "-fno-fast-math",
+          "-Wall", "-Wextra", "-shared", "-fPIC"]
+
+
+def build(force=True):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc"] + CFLAGS + [SRC, "-o", tmp, "-lm"])
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())
