@@ -1,0 +1,102 @@
+/*
+ * zc.h -- C ABI of libzc: fixed-rate compression of collective message buffers
+ * on MI355X (gfx950).
+ *
+ * The paper accelerates 3D-parallel + ZeRO LLM training by running every
+ * collective on compressed messages: a lossy fixed-rate codec of the ZFP family,
+ * at a low rate for data-parallel gradients and a higher rate for
+ * tensor/pipeline/ZeRO traffic (Sec. II-A, Sec. III-B and Table III, rates 8, 16,
+ * 24 in Sec. IV-C and IV-F), with the all-reduce built from a compressed
+ * reduce-scatter and all-gather (Sec. IV-A).  This library is the per-GPU part of
+ * that: compress a message, decompress a message, and the
+ * decompress-accumulate-recompress step of the reduce-scatter.
+ *
+ * Codec ("ZC-1"): the buffer is cut into blocks of 4 consecutive fp32 values; each
+ * block becomes exactly 4*rate bits = rate/2 bytes, stored back to back (block j at
+ * byte j*rate/2): one header byte (biased shared exponent, 0 = all-zero block) and
+ * 4*rate-8 payload bits produced by block-floating-point conversion, a reversible
+ * integer lifting transform, negabinary mapping and embedded bit-plane coding.
+ * A buffer whose length is not a multiple of 4 is padded by repeating its last
+ * value; the pad is dropped on decompression.
+ *
+ * Conventions for every call below
+ *   - Pointers named d_* are DEVICE pointers, owned by the caller, 16-byte aligned.
+ *     The library neither allocates, frees nor keeps them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue kernels on it and return without synchronising; buffers must stay
+ *     valid until that work has finished.
+ *   - Return value: ZC_OK or a negative error code; on error nothing is launched.
+ *   - n is a count of fp32 values.  n == 0 is valid and does nothing.
+ *   - Values that are not finite are outside the contract (the result is
+ *     unspecified, but no access leaves the buffers).
+ */
+#ifndef ZC_H
+#define ZC_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  ZC_OK = 0,
+  ZC_ERR_NULL = -1,     /* a required pointer is NULL */
+  ZC_ERR_RATE = -2,     /* rate not in {4,8,...,32} */
+  ZC_ERR_SIZE = -3,     /* n too large for this build (more than 2^40 values) */
+  ZC_ERR_CAPACITY = -4, /* out_cap smaller than zc_compressed_size(n, rate) */
+  ZC_ERR_K = -5,        /* k outside [1, 16] */
+  ZC_ERR_ALIGN = -6,    /* a device pointer is not 16-byte aligned */
+  ZC_ERR_LAUNCH = -7    /* the HIP runtime refused the launch */
+};
+
+/* Message classes of Table I / Table III. */
+enum zc_class {
+  ZC_DP_GRADIENT = 0,   /* data-parallel all-reduce */
+  ZC_TP_ACTIVATION = 1, /* tensor-parallel all-reduce / all-gather */
+  ZC_PP_ACTIVATION = 2, /* pipeline point-to-point */
+  ZC_ZERO_PARAM = 3,    /* ZeRO-1 parameter all-gather */
+  ZC_OPT_STATE = 4      /* ZeRO-1 reduce-scatter / optimizer-state traffic */
+};
+
+/* Library version, major*100 + minor. */
+int zc_version(void);
+
+/* Static description of an error code (never NULL). */
+const char* zc_strerror(int code);
+
+/* 1 if `rate` (bits per value) is supported: multiples of 4 from 4 to 32. */
+int zc_rate_supported(int rate);
+
+/* Rate of the hybrid scheme of Sec. III-B (Table III): low rate for
+ * data-parallel gradients (8, as in Sec. IV-F), high rate (16) for everything
+ * else.  Returns 0 for an unknown class. */
+int zc_rate_for_class(enum zc_class c);
+
+/* Bytes of the compressed form of n values: ceil(n/4) * rate/2, which is
+ * n*rate/8 when 4 divides n.  0 if the rate is unsupported. */
+size_t zc_compressed_size(size_t n, int rate);
+
+/* Compress d_in[0..n) into d_out[0..zc_compressed_size(n,rate)).
+ * d_out must not overlap d_in. */
+int zc_compress(const float* d_in, size_t n, int rate, void* d_out, size_t out_cap, void* stream);
+
+/* Decompress into d_out[0..n).  d_in holds zc_compressed_size(n,rate) bytes and may
+ * contain arbitrary bytes (every byte string decodes to something).  d_out must not
+ * overlap d_in. */
+int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stream);
+
+/* The reduce-scatter step (Sec. IV-A): d_in is a HOST array of k device pointers to
+ * compressed chunks of n values each (same rate).  Writes to d_out the compressed
+ * form of the element-wise fp32 sum ((x_0 + x_1) + x_2) + ... of the decompressed
+ * chunks; nothing but the k inputs and the output touches device memory.  The
+ * pointer array is read before the call returns.  d_out may be the same buffer as
+ * one of the inputs (each block is read before it is written) but must not
+ * partially overlap any. */
+int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, void* d_out,
+                         size_t out_cap, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZC_H */

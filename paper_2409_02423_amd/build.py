@@ -1,0 +1,34 @@
+"""Compile the HIP library (csrc/zc_kernels.hip) for gfx950 into libzc.so next to
+this file.  hipcc cross-compiles without a GPU."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "csrc", "zc_kernels.hip")
+DEPS = [SRC, os.path.join(HERE, "csrc", "zc_codec.h"), os.path.join(HERE, "..", "include", "zc.h")]
+LIB = os.path.join(HERE, "libzc.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    "-ffp-contract=off",                      # every fp32 operation rounds once, as written
+    "-fconstexpr-steps=200000000",            # the code tables are built at compile time
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def is_stale():
+    return not os.path.exists(LIB) or any(os.path.getmtime(d) > os.path.getmtime(LIB) for d in DEPS)
+
+
+def build(extra_flags=(), out=None):
+    out = out or LIB
+    tmp = out + ".tmp.%d" % os.getpid()
+    subprocess.check_call([HIPCC] + FLAGS + list(extra_flags) + [SRC, "-o", tmp])
+    os.replace(tmp, out)
+    return out
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,328 @@
+// zc_kernels.hip -- gfx950 kernels and the C ABI of libzc (see include/zc.h).
+//
+// Three streaming kernels, one lane per block of 4 values, grid-stride over the
+// buffer.  All are specialised per rate.  Each lane reads 16 contiguous bytes of
+// fp32 (compress) or RATE/2 contiguous bytes of stream (decompress, reduce), so a
+// wavefront touches one contiguous span per access; the code tables are staged in
+// LDS once per workgroup; the next block is fetched before the current one is
+// coded.  No matrix cores: nothing here is a contraction.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/zc.h"
+#include "zc_codec.h"
+
+namespace {
+
+__device__ const zc::EncTable g_enc_table = zc::build_enc_table();
+__device__ const zc::DecTable g_dec_table = zc::build_dec_table();
+
+constexpr int kThreads = 256;          // 4 wavefronts
+constexpr int kWorkgroupsPerCU = 8;    // grid cap: resident workgroups, each loops
+constexpr int kEncWords = 5 * 16;
+constexpr int kDecWords = 5 * 8 * 128;
+constexpr int kMaxChunks = 16;
+
+struct AnyLane {
+  __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
+};
+
+__device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table, int words) {
+  for (int i = threadIdx.x; i < words; i += kThreads) lds[i] = table[i];
+}
+
+// ---- block I/O ----------------------------------------------------------------------
+
+// Four values of block j as bit patterns; a ragged last block repeats the last value.
+__device__ __forceinline__ void load_values(const float* in, size_t n, size_t j, uint32_t (&x)[4]) {
+  if (4 * j + 4 <= n) {
+    uint4 v = reinterpret_cast<const uint4*>(in)[j];
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  } else {
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(in);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      size_t idx = 4 * j + i;
+      x[i] = w[idx < n ? idx : n - 1];
+    }
+  }
+}
+
+__device__ __forceinline__ void store_values(float* out, size_t n, size_t j, const float (&x)[4]) {
+  if (4 * j + 4 <= n) {
+    reinterpret_cast<float4*>(out)[j] = make_float4(x[0], x[1], x[2], x[3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (4 * j + i < n) out[4 * j + i] = x[i];
+  }
+}
+
+// Compressed block j: RATE/2 bytes at byte j*RATE/2; bits beyond the block are zero.
+template <int RATE>
+__device__ __forceinline__ void load_stream(const uint8_t* in, size_t j, uint32_t (&W)[zc::Traits<RATE>::kWords]) {
+  constexpr int B = zc::Traits<RATE>::kBlockBytes;
+  const uint8_t* p = in + j * B;
+  if constexpr (B == 16) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    W[0] = v.x; W[1] = v.y; W[2] = v.z; W[3] = v.w;
+  } else if constexpr (B == 8) {
+    uint2 v = *reinterpret_cast<const uint2*>(p);
+    W[0] = v.x; W[1] = v.y;
+  } else if constexpr (B % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < B / 4; ++i) W[i] = reinterpret_cast<const uint32_t*>(p)[i];
+  } else {
+    const uint16_t* h = reinterpret_cast<const uint16_t*>(p);
+#pragma unroll
+    for (int i = 0; i < zc::Traits<RATE>::kWords; ++i) W[i] = 0;
+#pragma unroll
+    for (int i = 0; i < B / 2; ++i) W[i / 2] |= (uint32_t)h[i] << (16 * (i % 2));
+  }
+}
+
+template <int RATE>
+__device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint32_t (&W)[zc::Traits<RATE>::kWords]) {
+  constexpr int B = zc::Traits<RATE>::kBlockBytes;
+  uint8_t* p = out + j * B;
+  if constexpr (B == 16) {
+    *reinterpret_cast<uint4*>(p) = make_uint4(W[0], W[1], W[2], W[3]);
+  } else if constexpr (B == 8) {
+    *reinterpret_cast<uint2*>(p) = make_uint2(W[0], W[1]);
+  } else if constexpr (B % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < B / 4; ++i) reinterpret_cast<uint32_t*>(p)[i] = W[i];
+  } else {
+    uint16_t* h = reinterpret_cast<uint16_t*>(p);
+#pragma unroll
+    for (int i = 0; i < B / 2; ++i) h[i] = (uint16_t)(W[i / 2] >> (16 * (i % 2)));
+  }
+}
+
+// ---- kernels ------------------------------------------------------------------------
+
+template <int RATE>
+__global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restrict__ in, size_t n,
+                                                            uint8_t* __restrict__ out) {
+  __shared__ uint32_t enc[kEncWords];
+  stage_table(enc, g_enc_table.v, kEncWords);
+  __syncthreads();
+  const size_t blocks = (n + 3) / 4;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= blocks) return;
+  uint32_t x[4];
+  load_values(in, n, j, x);
+  while (true) {
+    const size_t jn = j + stride;
+    uint32_t xn[4] = {0, 0, 0, 0};
+    if (jn < blocks) load_values(in, n, jn, xn);
+    uint32_t W[zc::Traits<RATE>::kWords];
+    zc::encode_block<RATE>(x, enc, W, AnyLane());
+    store_stream<RATE>(out, j, W);
+    if (jn >= blocks) break;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = xn[i];
+    j = jn;
+  }
+}
+
+template <int RATE>
+__global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __restrict__ in, size_t n,
+                                                              float* __restrict__ out) {
+  __shared__ uint32_t dec[kDecWords];
+  stage_table(dec, g_dec_table.v, kDecWords);
+  __syncthreads();
+  const size_t blocks = (n + 3) / 4;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= blocks) return;
+  constexpr int NW = zc::Traits<RATE>::kWords;
+  uint32_t W[NW];
+  load_stream<RATE>(in, j, W);
+  while (true) {
+    const size_t jn = j + stride;
+    uint32_t Wn[NW];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) Wn[i] = 0;
+    if (jn < blocks) load_stream<RATE>(in, jn, Wn);
+    float y[4];
+    zc::decode_block<RATE>(W, dec, y, AnyLane());
+    store_values(out, n, j, y);
+    if (jn >= blocks) break;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) W[i] = Wn[i];
+    j = jn;
+  }
+}
+
+struct ChunkPointers {
+  const uint8_t* p[kMaxChunks];
+};
+
+// Decode block j of every chunk, add in fp32 in chunk order, encode the sum.  The
+// output may be one of the inputs: a lane reads its block of all chunks before it
+// writes, and no other lane touches that block.
+template <int RATE>
+__global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, size_t n, uint8_t* out) {
+  __shared__ uint32_t dec[kDecWords];
+  __shared__ uint32_t enc[kEncWords];
+  stage_table(dec, g_dec_table.v, kDecWords);
+  stage_table(enc, g_enc_table.v, kEncWords);
+  __syncthreads();
+  const size_t blocks = (n + 3) / 4;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  constexpr int NW = zc::Traits<RATE>::kWords;
+  for (size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x; j < blocks; j += stride) {
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < k; ++c) {
+      uint32_t W[NW];
+      load_stream<RATE>(chunks.p[c], j, W);
+      float y[4];
+      zc::decode_block<RATE>(W, dec, y, AnyLane());
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
+    }
+    uint32_t x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // the result is compress(sum): pad lanes of a ragged last block repeat the last valid sum
+      size_t idx = 4 * j + i;
+      float v = idx < n ? s[i] : s[(n - 1) & 3];
+      x[i] = __float_as_uint(v);
+    }
+    uint32_t W[NW];
+    zc::encode_block<RATE>(x, enc, W, AnyLane());
+    store_stream<RATE>(out, j, W);
+  }
+}
+
+// ---- host side ----------------------------------------------------------------------
+
+int grid_cap() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256 * kWorkgroupsPerCU;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cached[dev] = cus * kWorkgroupsPerCU;
+  }
+  return cached[dev];
+}
+
+unsigned grid_for(size_t n) {
+  size_t blocks = (n + 3) / 4;
+  size_t groups = (blocks + kThreads - 1) / kThreads;
+  size_t cap = (size_t)grid_cap();
+  return (unsigned)(groups < cap ? groups : cap);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr size_t kMaxValues = (size_t)1 << 40;
+
+int finish_launch() { return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH; }
+
+}  // namespace
+
+#define ZC_DISPATCH_RATE(rate, CALL) \
+  switch (rate) {                    \
+    case 4: CALL(4); break;          \
+    case 8: CALL(8); break;          \
+    case 12: CALL(12); break;        \
+    case 16: CALL(16); break;        \
+    case 20: CALL(20); break;        \
+    case 24: CALL(24); break;        \
+    case 28: CALL(28); break;        \
+    case 32: CALL(32); break;        \
+    default: return ZC_ERR_RATE;     \
+  }
+
+extern "C" {
+
+int zc_version(void) { return 100; }
+
+const char* zc_strerror(int code) {
+  switch (code) {
+    case ZC_OK: return "ok";
+    case ZC_ERR_NULL: return "null pointer";
+    case ZC_ERR_RATE: return "unsupported rate (use a multiple of 4 between 4 and 32)";
+    case ZC_ERR_SIZE: return "buffer too large";
+    case ZC_ERR_CAPACITY: return "output capacity smaller than zc_compressed_size(n, rate)";
+    case ZC_ERR_K: return "number of chunks outside [1, 16]";
+    case ZC_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case ZC_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+int zc_rate_supported(int rate) { return rate >= 4 && rate <= 32 && rate % 4 == 0; }
+
+int zc_rate_for_class(enum zc_class c) {
+  switch (c) {
+    case ZC_DP_GRADIENT: return 8;
+    case ZC_TP_ACTIVATION:
+    case ZC_PP_ACTIVATION:
+    case ZC_ZERO_PARAM:
+    case ZC_OPT_STATE: return 16;
+    default: return 0;
+  }
+}
+
+size_t zc_compressed_size(size_t n, int rate) {
+  if (!zc_rate_supported(rate)) return 0;
+  return (n / 4 + (n % 4 ? 1 : 0)) * (size_t)(rate / 2);
+}
+
+int zc_compress(const float* d_in, size_t n, int rate, void* d_out, size_t out_cap, void* stream) {
+  if (!zc_rate_supported(rate)) return ZC_ERR_RATE;
+  if (n == 0) return ZC_OK;
+  if (!d_in || !d_out) return ZC_ERR_NULL;
+  if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (n > kMaxValues) return ZC_ERR_SIZE;
+  if (out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(R) hipLaunchKernelGGL(compress_kernel<R>, dim3(grid_for(n)), dim3(kThreads), 0, s, d_in, n, static_cast<uint8_t*>(d_out))
+  ZC_DISPATCH_RATE(rate, CALL)
+#undef CALL
+  return finish_launch();
+}
+
+int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stream) {
+  if (!zc_rate_supported(rate)) return ZC_ERR_RATE;
+  if (n == 0) return ZC_OK;
+  if (!d_in || !d_out) return ZC_ERR_NULL;
+  if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (n > kMaxValues) return ZC_ERR_SIZE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(R) hipLaunchKernelGGL(decompress_kernel<R>, dim3(grid_for(n)), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), n, d_out)
+  ZC_DISPATCH_RATE(rate, CALL)
+#undef CALL
+  return finish_launch();
+}
+
+int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, void* d_out, size_t out_cap,
+                         void* stream) {
+  if (!zc_rate_supported(rate)) return ZC_ERR_RATE;
+  if (k < 1 || k > kMaxChunks) return ZC_ERR_K;
+  if (n == 0) return ZC_OK;
+  if (!d_in || !d_out) return ZC_ERR_NULL;
+  ChunkPointers chunks;
+  for (int c = 0; c < kMaxChunks; ++c) chunks.p[c] = nullptr;
+  for (int c = 0; c < k; ++c) {
+    if (!d_in[c]) return ZC_ERR_NULL;
+    if (!aligned16(d_in[c])) return ZC_ERR_ALIGN;
+    chunks.p[c] = static_cast<const uint8_t*>(d_in[c]);
+  }
+  if (!aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (n > kMaxValues) return ZC_ERR_SIZE;
+  if (out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(R) hipLaunchKernelGGL(reduce_kernel<R>, dim3(grid_for(n)), dim3(kThreads), 0, s, chunks, k, n, static_cast<uint8_t*>(d_out))
+  ZC_DISPATCH_RATE(rate, CALL)
+#undef CALL
+  return finish_launch();
+}
+
+}  // extern "C"

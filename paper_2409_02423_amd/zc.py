@@ -1,0 +1,150 @@
+"""Python binding of libzc (include/zc.h): argument marshalling only.
+
+Every function has the name and meaning of the C entry point it calls; tensors
+are torch CUDA tensors used as device memory, and the kernels are enqueued on
+torch's current stream unless a stream is given.  There is no fallback: if the
+HIP library cannot be loaded, every call raises.
+"""
+import ctypes
+import os
+
+import torch  # loads the HIP runtime that libzc.so binds to
+
+from . import build as _build
+
+ZC_OK = 0
+ZC_ERR_NULL, ZC_ERR_RATE, ZC_ERR_SIZE, ZC_ERR_CAPACITY = -1, -2, -3, -4
+ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH = -5, -6, -7
+ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE = range(5)
+
+EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
+           "zc_compress", "zc_decompress", "zc_reduce_compressed")
+
+_lib = None
+
+
+class ZcError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__("%s failed: %s (%d)" % (what, zc_strerror(code), code))
+        self.code = code
+
+
+def library_path():
+    return _build.LIB
+
+
+def lib():
+    """The loaded C library.  Builds it first only if no built library exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = ctypes.CDLL(_build.LIB)
+        L.zc_version.restype = ctypes.c_int
+        L.zc_strerror.restype = ctypes.c_char_p
+        L.zc_strerror.argtypes = [ctypes.c_int]
+        L.zc_rate_supported.argtypes = [ctypes.c_int]
+        L.zc_rate_for_class.argtypes = [ctypes.c_int]
+        L.zc_compressed_size.restype = ctypes.c_size_t
+        L.zc_compressed_size.argtypes = [ctypes.c_size_t, ctypes.c_int]
+        L.zc_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
+                                  ctypes.c_size_t, ctypes.c_void_p]
+        L.zc_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
+                                    ctypes.c_void_p]
+        L.zc_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t,
+                                           ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+def zc_version():
+    return int(lib().zc_version())
+
+
+def zc_strerror(code):
+    return lib().zc_strerror(int(code)).decode()
+
+
+def zc_rate_supported(rate):
+    return bool(lib().zc_rate_supported(int(rate)))
+
+
+def zc_rate_for_class(message_class):
+    return int(lib().zc_rate_for_class(int(message_class)))
+
+
+def zc_compressed_size(n, rate):
+    return int(lib().zc_compressed_size(int(n), int(rate)))
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_device_tensor(t, dtype, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (what, dtype))
+
+
+def _new_stream_buffer(n, rate, device):
+    size = zc_compressed_size(n, rate)
+    if size == 0 and n != 0:
+        raise ZcError(ZC_ERR_RATE, "zc_compressed_size")
+    return torch.empty(size, dtype=torch.uint8, device=device)
+
+
+def zc_compress(d_in, rate, d_out=None, stream=None):
+    """fp32 CUDA tensor -> uint8 CUDA tensor of zc_compressed_size(n, rate) bytes."""
+    _check_device_tensor(d_in, torch.float32, "d_in")
+    n = d_in.numel()
+    if d_out is None:
+        d_out = _new_stream_buffer(n, rate, d_in.device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zc_compress(d_in.data_ptr(), n, int(rate), d_out.data_ptr(), d_out.numel(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_compress")
+    return d_out
+
+
+def zc_decompress(d_in, n, rate, d_out=None, stream=None):
+    """uint8 CUDA tensor holding the compressed form of n values -> fp32 CUDA tensor."""
+    _check_device_tensor(d_in, torch.uint8, "d_in")
+    need = zc_compressed_size(n, rate)
+    if need == 0 and n != 0:
+        raise ZcError(ZC_ERR_RATE, "zc_decompress")
+    if d_in.numel() < need:
+        raise ValueError("d_in holds %d bytes, %d values at rate %d need %d" % (d_in.numel(), n, rate, need))
+    if d_out is None:
+        d_out = torch.empty(n, dtype=torch.float32, device=d_in.device)
+    _check_device_tensor(d_out, torch.float32, "d_out")
+    if d_out.numel() < n:
+        raise ValueError("d_out holds %d values, need %d" % (d_out.numel(), n))
+    rc = lib().zc_decompress(d_in.data_ptr(), int(n), int(rate), d_out.data_ptr(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_decompress")
+    return d_out
+
+
+def zc_reduce_compressed(d_in, n, rate, d_out=None, stream=None):
+    """List of k uint8 CUDA tensors (compressed chunks of n values) -> compressed sum."""
+    chunks = list(d_in)
+    need = zc_compressed_size(n, rate)
+    if need == 0 and n != 0:
+        raise ZcError(ZC_ERR_RATE, "zc_reduce_compressed")
+    for c in chunks:
+        _check_device_tensor(c, torch.uint8, "every chunk")
+        if c.numel() < need:
+            raise ValueError("a chunk holds %d bytes, need %d" % (c.numel(), need))
+    if d_out is None:
+        device = chunks[0].device if chunks else torch.device("cuda")
+        d_out = _new_stream_buffer(n, rate, device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    k = len(chunks)
+    ptrs = (ctypes.c_void_p * max(k, 1))(*[c.data_ptr() for c in chunks])
+    rc = lib().zc_reduce_compressed(ptrs, k, int(n), int(rate), d_out.data_ptr(), d_out.numel(),
+                                    _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_reduce_compressed")
+    return d_out

@@ -1,0 +1,50 @@
+// Host build of the per-block codec that the GPU kernels run (csrc/zc_codec.h), so
+// that its logic can be checked on the CPU against the reference codec and under
+// host sanitizers before it runs on a GPU.  Test-only: the library never runs this.
+#include <cstring>
+
+#include "../../paper_2409_02423_amd/csrc/zc_codec.h"
+
+namespace {
+const zc::EncTable kEnc = zc::build_enc_table();
+const zc::DecTable kDec = zc::build_dec_table();
+auto always = [](bool p) { return p; };
+
+template <int RATE>
+void enc(const float* x, uint8_t* out) {
+  uint32_t b[4], W[zc::Traits<RATE>::kWords];
+  std::memcpy(b, x, 16);
+  zc::encode_block<RATE>(b, kEnc.v, W, always);
+  std::memcpy(out, W, zc::Traits<RATE>::kBlockBytes);
+}
+template <int RATE>
+void dec(const uint8_t* in, float* x) {
+  uint32_t W[zc::Traits<RATE>::kWords] = {};
+  std::memcpy(W, in, zc::Traits<RATE>::kBlockBytes);
+  float o[4];
+  zc::decode_block<RATE>(W, kDec.v, o, always);
+  std::memcpy(x, o, 16);
+}
+}  // namespace
+
+#define ZC_FOR_RATES(F) F(4) F(8) F(12) F(16) F(20) F(24) F(28) F(32)
+
+extern "C" int zc_host_encode_blocks(int rate, const float* x, size_t blocks, uint8_t* out) {
+  for (size_t j = 0; j < blocks; ++j) switch (rate) {
+#define F(R) case R: enc<R>(x + 4 * j, out + j * (R / 2)); break;
+      ZC_FOR_RATES(F)
+#undef F
+      default: return -2;
+    }
+  return 0;
+}
+
+extern "C" int zc_host_decode_blocks(int rate, const uint8_t* in, size_t blocks, float* x) {
+  for (size_t j = 0; j < blocks; ++j) switch (rate) {
+#define F(R) case R: dec<R>(in + j * (R / 2), x + 4 * j); break;
+      ZC_FOR_RATES(F)
+#undef F
+      default: return -2;
+    }
+  return 0;
+}

@@ -1,0 +1,83 @@
+"""The C-ABI library loads, exports every symbol include/zc.h declares, and its
+host-side logic (sizes, policy, error codes) behaves as documented.  No kernel is
+launched here: every call below returns before reaching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2409_02423_amd import zc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "zc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(zc_[a-z_]+)\s*\(", text))
+    assert declared == set(zc.EXPORTS)
+    L = ctypes.CDLL(zc.library_path()) if os.path.exists(zc.library_path()) else zc.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_sizes_and_policy():
+    assert zc.zc_version() >= 100
+    for rate in range(-4, 40):
+        ok = rate in (4, 8, 12, 16, 20, 24, 28, 32)
+        assert zc.zc_rate_supported(rate) == ok
+        assert zc.zc_compressed_size(1024, rate) == (1024 * rate // 8 if ok else 0)
+    assert zc.zc_compressed_size(0, 8) == 0
+    assert zc.zc_compressed_size(1, 4) == 2 and zc.zc_compressed_size(5, 4) == 4
+    assert zc.zc_compressed_size(7, 24) == 24
+    assert zc.zc_compressed_size(1 << 28, 4) == 1 << 27
+    # low rate for data-parallel gradients, high rate for the rest (Table III)
+    assert zc.zc_rate_for_class(zc.ZC_DP_GRADIENT) == 8
+    for c in (zc.ZC_TP_ACTIVATION, zc.ZC_PP_ACTIVATION, zc.ZC_ZERO_PARAM, zc.ZC_OPT_STATE):
+        assert zc.zc_rate_for_class(c) == 16
+    assert zc.zc_rate_for_class(99) == 0
+
+
+def test_error_strings():
+    seen = set()
+    for code in range(0, -8, -1):
+        s = zc.zc_strerror(code)
+        assert s and s != "unknown error code"
+        seen.add(s)
+    assert len(seen) == 8
+    assert zc.zc_strerror(-99) == "unknown error code"
+
+
+def test_argument_errors_come_before_any_launch():
+    L = zc.lib()
+    good, odd = 0x10000, 0x10004  # never dereferenced: every call fails validation first
+    assert L.zc_compress(good, 16, 7, good, 100, None) == zc.ZC_ERR_RATE
+    assert L.zc_compress(None, 0, 8, None, 0, None) == zc.ZC_OK          # n == 0: nothing to do
+    assert L.zc_compress(None, 16, 8, good, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc_compress(good, 16, 8, None, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc_compress(odd, 16, 8, good, 100, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_compress(good, 16, 8, odd, 100, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_compress(good, 16, 8, good, 15, None) == zc.ZC_ERR_CAPACITY
+    assert L.zc_compress(good, (1 << 40) + 4, 8, good, 1 << 62, None) == zc.ZC_ERR_SIZE
+    assert L.zc_decompress(good, 16, 5, good, None) == zc.ZC_ERR_RATE
+    assert L.zc_decompress(None, 16, 8, good, None) == zc.ZC_ERR_NULL
+    assert L.zc_decompress(good, 16, 8, odd, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_decompress(None, 0, 8, None, None) == zc.ZC_OK
+    two = (ctypes.c_void_p * 2)(good, good)
+    assert L.zc_reduce_compressed(two, 0, 16, 8, good, 100, None) == zc.ZC_ERR_K
+    assert L.zc_reduce_compressed(two, 17, 16, 8, good, 100, None) == zc.ZC_ERR_K
+    assert L.zc_reduce_compressed(two, 2, 16, 3, good, 100, None) == zc.ZC_ERR_RATE
+    assert L.zc_reduce_compressed(two, 2, 16, 8, good, 15, None) == zc.ZC_ERR_CAPACITY
+    assert L.zc_reduce_compressed(None, 2, 16, 8, good, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc_reduce_compressed((ctypes.c_void_p * 2)(good, None), 2, 16, 8, good, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc_reduce_compressed((ctypes.c_void_p * 2)(good, odd), 2, 16, 8, good, 100, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_reduce_compressed(two, 2, 0, 8, None, 0, None) == zc.ZC_OK
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        zc.zc_compress(torch.zeros(8), 8)
+    with pytest.raises(TypeError):
+        zc.zc_decompress(torch.zeros(8, dtype=torch.uint8), 8, 8)
