@@ -1,0 +1,272 @@
+#!/usr/bin/env python3
+"""Benchmark of the compressed-collective hot path on one MI355X.
+
+One step = one pass of the whole path over one message buffer, as a rank in a
+compressed ring all-reduce performs it (Sec. IV-A):
+    zc_compress(local gradients)            fp32 -> stream
+    zc_reduce_compressed([incoming, local]) decompress + add + recompress, fused
+    zc_decompress(result)                   stream -> fp32
+Workload: the data-parallel gradient bucket (2^28 fp32 values with low-rank
+structure, rate 4), synthetic and seeded, resident in HBM before timing starts.
+`value` is GB/s of uncompressed fp32 pushed through the whole step (4*n / step time).
+
+Prints ONE JSON line on stdout.  --sweep adds per-kernel figures for all five
+configurations on stderr (and in gpurun_out/sweep.json when that folder exists).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
+INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one int32 op per lane-clock
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# workload (profiles/), scaled by the same counters on a copy of known size.
+# None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(kernel, n, rate, k=2):
+    """Bytes the method itself must move per launch: 4 + R/8 per value for
+    compress and decompress, (k + 1) * R/8 per value for the k-way reduce."""
+    if kernel in ("compress", "decompress"):
+        return n * 4 + n * rate // 8
+    return (k + 1) * (n * rate // 8)
+
+
+def time_events(fn, reps, torch):
+    """Per-call durations (ms) measured with HIP events on the launch stream."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in evs]
+
+
+def cpu_baseline(x_host, rate, sample_values, threads):
+    """The CPU reference, as it stands, on the first `sample_values` values: the
+    same three calls as one GPU step.  Blocks are independent, so `threads`
+    workers each take a contiguous run of blocks."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import zc_ref
+    n = min(sample_values, x_host.size) // 4 * 4
+    xs = x_host[:n]
+    peer = np.ascontiguousarray(xs[::-1])
+
+    def work(part):
+        cp = zc_ref.compress(part[1], rate)  # the incoming chunk (not timed as part of the step)
+        t0 = time.perf_counter()
+        c = zc_ref.compress(part[0], rate)
+        r = zc_ref.reduce_compressed([cp, c], part[0].size, rate)
+        zc_ref.decompress(r, part[0].size, rate)
+        return time.perf_counter() - t0
+
+    def run(nthreads):
+        bounds = [(n // 4 * i // nthreads) * 4 for i in range(nthreads + 1)]
+        parts = [(xs[a:b], peer[a:b]) for a, b in zip(bounds[:-1], bounds[1:])]
+        t0 = time.perf_counter()
+        if nthreads == 1:
+            inner = [work(parts[0])]
+        else:
+            with ThreadPoolExecutor(nthreads) as ex:
+                inner = list(ex.map(work, parts))
+        wall = time.perf_counter() - t0
+        # the untimed pre-compression of the incoming chunk is excluded via the inner clocks
+        return max(inner), wall
+
+    t1, _ = run(1)
+    out = {"value": round(4 * n / t1 / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "sample": "first %d values of the workload buffer, same three calls as one step" % n}
+    if threads > 1:
+        tn, _ = run(threads)
+        out["all_cores"] = {"value": round(4 * n / tn / 1e9, 4), "cores": threads}
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-log2", type=int, default=26)
+    ap.add_argument("--sweep", action="store_true", help="also time every kernel on all five configurations")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device copies of the 1 GiB input (known traffic, for scaling profiler counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2409_02423_amd import workloads, zc
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    zc.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = workloads.CONFIGS[2]
+    rate, n = cfg["rate"], cfg["n"]
+    x_host = workloads.config_buffers(2)[0][1]
+    x = torch.from_numpy(x_host).to(dev)
+    peer_host = workloads.gradient_lowrank(6144, 43690, tail=n - 6144 * 43690, config=2, index=1)
+    incoming = zc.zc_compress(torch.from_numpy(peer_host).to(dev), rate)
+    del peer_host
+    c = torch.empty(zc.zc_compressed_size(n, rate), dtype=torch.uint8, device=dev)
+    r = torch.empty_like(c)
+    y = torch.empty(n, dtype=torch.float32, device=dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        e = [ev() for _ in range(4)] if record else None
+        if record:
+            e[0].record()
+        zc.zc_compress(x, rate, d_out=c)
+        if record:
+            e[1].record()
+        zc.zc_reduce_compressed([incoming, c], n, rate, d_out=r)
+        if record:
+            e[2].record()
+        zc.zc_decompress(r, n, rate, d_out=y)
+        if record:
+            e[3].record()
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    if args.calibrate_copy:
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+    names = ("compress", "reduce", "decompress")
+    avg_ms = {nm: float(np.mean([m[i].elapsed_time(m[i + 1]) for m in marks])) for i, nm in enumerate(names)}
+    dominant = max(avg_ms, key=avg_ms.get)
+    abytes = algorithmic_bytes(dominant, n, rate, k=2)
+    achieved = abytes / (avg_ms[dominant] * 1e-3) / 1e9
+    roofline = {"kernel": dominant + "_kernel<%d>" % rate, "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_launch_ms": round(avg_ms[dominant], 4),
+                "algorithmic_bytes": abytes}
+    kernels = {nm: {"avg_ms": round(avg_ms[nm], 4),
+                    "uncompressed_GBps": round(4 * n / (avg_ms[nm] * 1e-3) / 1e9, 1),
+                    "algorithmic_GBps": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9, 1),
+                    "hbm_frac": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+               for nm in names}
+
+    # error of the lossy round trip against the original input (reported, not a target)
+    back = zc.zc_decompress(c, n, rate)
+    err = (back - x).double()
+    quality = {"max_abs_err": float(err.abs().max()), "rmse": float(err.pow(2).mean().sqrt()),
+               "input_std": float(x.double().std())}
+    del back, err
+
+    result = {
+        "metric": "compress/decompress/reduce GB/s (uncompressed fp32) and % of HBM peak",
+        "value": round(4 * n / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
+                               "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
+        "kernels": kernels, "roofline": roofline, "round_trip_error": quality,
+    }
+
+    if args.sweep:
+        result_sweep = sweep(torch, zc, workloads, dev)
+        print(json.dumps(result_sweep, indent=1), file=sys.stderr)
+        if os.path.isdir("gpurun_out"):
+            with open("gpurun_out/sweep.json", "w") as f:
+                json.dump(result_sweep, f, indent=1)
+
+    if not args.no_cpu_baseline:
+        del y, r
+        torch.cuda.empty_cache()
+        threads = min(16, len(os.sched_getaffinity(0)))
+        result["cpu_baseline"] = cpu_baseline(x_host, rate, 1 << args.cpu_sample_log2, threads)
+    print(json.dumps(result))
+
+
+def sweep(torch, zc, workloads, dev):
+    """Per-kernel timings on all five configurations (each buffer rotated through
+    enough copies that the working set exceeds the 256 MB last-level cache)."""
+    out = []
+    for config in (1, 2, 3, 4, 5):
+        rate = workloads.CONFIGS[config]["rate"]
+        bufs = workloads.config_buffers(config)
+        if config == 5:
+            n = bufs[0][1].size
+            comp = [zc.zc_compress(torch.from_numpy(b).to(dev), rate) for _, b in bufs]
+            acc = comp[0].clone()
+            final = torch.empty(n, dtype=torch.float32, device=dev)
+
+            def chain():
+                acc.copy_(comp[0])
+                for j in range(1, 8):
+                    zc.zc_reduce_compressed([acc, comp[j]], n, rate, d_out=acc)
+                zc.zc_decompress(acc, n, rate, d_out=final)
+
+            ms = time_events(chain, 20, torch)[3:]
+            one = time_events(lambda: zc.zc_reduce_compressed([acc, comp[1]], n, rate, d_out=acc), 40, torch)[5:]
+            k8 = time_events(lambda: zc.zc_reduce_compressed(comp, n, rate, d_out=acc), 20, torch)[3:]
+            out.append({"config": 5, "rate": rate, "n": n,
+                        "ring_chain_7_reduces_plus_decompress_ms": float(np.median(ms)),
+                        "reduce_k2_ms": float(np.median(one)),
+                        "reduce_k2_uncompressed_GBps": 4 * n / (float(np.median(one)) * 1e-3) / 1e9,
+                        "reduce_k2_algorithmic_GBps": algorithmic_bytes("reduce", n, rate, 2) / (float(np.median(one)) * 1e-3) / 1e9,
+                        "reduce_k8_ms": float(np.median(k8)),
+                        "reduce_k8_algorithmic_GBps": algorithmic_bytes("reduce", n, rate, 8) / (float(np.median(k8)) * 1e-3) / 1e9,
+                        "note": "working set 16 MiB per chunk: served from the last-level cache, not HBM"})
+            continue
+        for label, b in bufs:
+            n = b.size
+            copies = max(1, int(np.ceil((1 << 29) / (4 * n))))
+            xs = [torch.from_numpy(b).to(dev) for _ in range(min(copies, 8))]
+            cs = [zc.zc_compress(x, rate) for x in xs]
+            ys = [torch.empty_like(x) for x in xs]
+            it = [0]
+
+            def comp_fn():
+                i = it[0] % len(xs)
+                it[0] += 1
+                zc.zc_compress(xs[i], rate, d_out=cs[i])
+
+            def dec_fn():
+                i = it[0] % len(xs)
+                it[0] += 1
+                zc.zc_decompress(cs[i], n, rate, d_out=ys[i])
+
+            tc = float(np.median(time_events(comp_fn, 24, torch)[4:]))
+            td = float(np.median(time_events(dec_fn, 24, torch)[4:]))
+            err = (ys[0] - xs[0]).double()
+            ab = algorithmic_bytes("compress", n, rate)
+            out.append({"config": config, "buffer": label, "rate": rate, "n": n, "rotated_copies": len(xs),
+                        "compress_ms": tc, "decompress_ms": td,
+                        "compress_uncompressed_GBps": 4 * n / (tc * 1e-3) / 1e9,
+                        "decompress_uncompressed_GBps": 4 * n / (td * 1e-3) / 1e9,
+                        "compress_hbm_frac": ab / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "decompress_hbm_frac": ab / (td * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "max_abs_err": float(err.abs().max()), "rmse": float(err.pow(2).mean().sqrt()),
+                        "input_std": float(xs[0].double().std())})
+            del xs, cs, ys, err
+            torch.cuda.empty_cache()
+    return out
+
+
+if __name__ == "__main__":
+    main()
