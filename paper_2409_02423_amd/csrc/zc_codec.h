@@ -109,41 +109,53 @@ static_assert(transpose_8x4(transpose_4x8(0x7E57AB1Eu)) == 0x7E57AB1Eu, "transpo
 
 // ---- code tables -------------------------------------------------------------------
 
-// Encoder: entry[(n*16 + plane bits)] = code word | length << 8 | (byte offset of the
-// next state's 16 entries) << 16.  Plane bit i belongs to coefficient i; the code
-// word's bit 0 is written first.
-struct EncTable { uint32_t v[5 * 16]; };
+// One plane of the embedded code in state n (number of leading coefficients already
+// significant): n verbatim bits, then group tests over the rest.  Plane bit i belongs
+// to coefficient i; bit 0 of the code word is written first.
+struct PlaneCode { uint32_t code; int len; int next; };
+
+constexpr PlaneCode code_one_plane(int n, int p) {
+  uint32_t code = 0;
+  int len = 0;
+  for (int i = 0; i < n; ++i) code |= (uint32_t)((p >> i) & 1) << len++;
+  int i = n;
+  while (i < 4) {
+    int any = (p >> i) != 0;
+    code |= (uint32_t)any << len++;
+    if (!any) break;
+    while (i < 3) {  // position of the first one; the last index needs no bit
+      int b = (p >> i) & 1;
+      code |= (uint32_t)b << len++;
+      if (b) break;
+      ++i;
+    }
+    ++i;
+  }
+  return PlaneCode{code, len, i};
+}
+
+// Encoder, two planes per step: entry[n*256 + (second plane << 4 | first plane)] =
+// code word (<= 14 bits) | length << 14 | (byte offset of the next state's 256
+// entries) << 18.
+struct EncTable { uint32_t v[5 * 256]; };
 
 constexpr EncTable build_enc_table() {
   EncTable t{};
   for (int n = 0; n <= 4; ++n)
-    for (int p = 0; p < 16; ++p) {
-      uint32_t code = 0;
-      int len = 0;
-      for (int i = 0; i < n; ++i) code |= (uint32_t)((p >> i) & 1) << len++;
-      int i = n;
-      while (i < 4) {
-        int any = (p >> i) != 0;
-        code |= (uint32_t)any << len++;
-        if (!any) break;
-        while (i < 3) {  // position of the first one; the last index needs no bit
-          int b = (p >> i) & 1;
-          code |= (uint32_t)b << len++;
-          if (b) break;
-          ++i;
-        }
-        ++i;
-      }
-      t.v[n * 16 + p] = code | (uint32_t)len << 8 | (uint32_t)(i * 16 * 4) << 16;
+    for (int pp = 0; pp < 256; ++pp) {
+      PlaneCode a = code_one_plane(n, pp & 15);
+      PlaneCode b = code_one_plane(a.next, pp >> 4);
+      t.v[n * 256 + pp] = (a.code | b.code << a.len) | (uint32_t)(a.len + b.len) << 14 |
+                          (uint32_t)(b.next * 256 * 4) << 18;
     }
   return t;
 }
 
-// Decoder: entry[(n*8 + min(bits left, 7))*128 + next 7 stream bits] =
-// plane bits | bits consumed << 4 | (byte offset of the next state's 8*128 entries)
-// << 16.  With fewer than 7 bits left the stream bits beyond the budget are ignored,
-// and a group known to hold a one that the budget cut before it was located gets the
-// one at the lowest index still possible.
+// Decoder, one plane per step: entry[(n*8 + min(bits left, 7))*128 + next 7 stream
+// bits] = plane bits | bits consumed << 4 | (byte offset of the next state's 8*128
+// entries) << 16.  With fewer than 7 bits left the stream bits beyond the budget are
+// ignored, and a group known to hold a one that the budget cut before it was located
+// gets the one at the lowest index still possible.
 struct DecTable { uint32_t v[5 * 8 * 128]; };
 
 constexpr DecTable build_dec_table() {
@@ -227,28 +239,22 @@ ZC_DEV void shift_out(uint32_t (&W)[NW], uint32_t len) {
 
 // ---- forward path ------------------------------------------------------------------
 
+ZC_DEV float bits_to_float(uint32_t b) { return __builtin_bit_cast(float, b); }
+
 // Four fp32 bit patterns -> biased block exponent E and the four negabinary
-// coefficient words.  E = max exponent field + 1 (1 for a subnormal-only block, 0
-// for an all-zero block); q_i = sign * ((significand << 5) >> (E - max(field,1))),
-// which is x_i * 2^(28 - (E - 127)) truncated toward zero.
+// coefficient words.  With m the largest magnitude as a bit pattern, E = (exponent
+// field of m) + (m != 0): field + 1 for a normal maximum, 1 for a subnormal-only
+// block, 0 for an all-zero block.  q_i = x_i * 2^(155 - E) truncated toward zero: the
+// scaling is exact in fp32 (a result below 2^-126 may round, but truncates to 0 either
+// way) and the float -> int conversion truncates.
 ZC_DEV void forward_transform(const uint32_t (&x)[4], uint32_t& E, uint32_t (&u)[4]) {
-  uint32_t f[4], fmax = 0, any = 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    f[i] = (x[i] >> 23) & 0xFFu;
-    fmax = umax(fmax, f[i]);
-    any |= x[i];
-  }
-  E = fmax ? fmax + 1u : ((any & 0x7FFFFFFFu) ? 1u : 0u);
-  int32_t q[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t sig = (x[i] & 0x7FFFFFu) | (f[i] ? 0x800000u : 0u);
-    uint32_t sh = umin(E - umax(f[i], 1u), 31u);  // E = 0 wraps to 31; sig is 0 then
-    int32_t mag = (int32_t)((sig << 5) >> sh);
-    q[i] = (x[i] >> 31) ? -mag : mag;
-  }
-  int32_t a = q[0], b = q[1], c = q[2], d = q[3];
+  uint32_t m = umax(umax(x[0] & 0x7FFFFFFFu, x[1] & 0x7FFFFFFFu), umax(x[2] & 0x7FFFFFFFu, x[3] & 0x7FFFFFFFu));
+  E = (m >> 23) + (m != 0u ? 1u : 0u);
+  const int scale = 127 + kFractionBits - (int)E;
+  int32_t a = (int32_t)__builtin_ldexpf(bits_to_float(x[0]), scale);
+  int32_t b = (int32_t)__builtin_ldexpf(bits_to_float(x[1]), scale);
+  int32_t c = (int32_t)__builtin_ldexpf(bits_to_float(x[2]), scale);
+  int32_t d = (int32_t)__builtin_ldexpf(bits_to_float(x[3]), scale);
   d -= a; a += d >> 1;
   b -= c; c += b >> 1;
   c -= a; a += c >> 1;
@@ -262,7 +268,7 @@ ZC_DEV void forward_transform(const uint32_t (&x)[4], uint32_t& E, uint32_t (&u)
 
 // Byte `j` of each of four words, packed (word i -> byte i), then transposed so that
 // nibble m holds bit 8*j + m of the four words.
-ZC_DEV uint32_t gather_planes(const uint32_t (&r)[4], int j) {
+ZC_DEV uint32_t gather_planes(const uint32_t (&r)[4], uint32_t j) {
   uint32_t g = ((r[0] >> (8 * j)) & 0xFFu) | (((r[1] >> (8 * j)) & 0xFFu) << 8) |
                (((r[2] >> (8 * j)) & 0xFFu) << 16) | (((r[3] >> (8 * j)) & 0xFFu) << 24);
   return transpose_4x8(g);
@@ -275,6 +281,9 @@ template <int RATE, class AnyActive>
 ZC_DEV void encode_block(const uint32_t (&x)[4], const uint32_t* enc, uint32_t (&W)[Traits<RATE>::kWords],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
+  // every plane costs at least one bit, so at most this many planes are ever coded
+  constexpr int kMaxPlanes = Traits<RATE>::kPayloadBits < 32 ? Traits<RATE>::kPayloadBits : 32;
+  constexpr int kMaxSteps = (kMaxPlanes + 1) / 2;
   uint32_t E, u[4];
   forward_transform(x, E, u);
   // leading empty planes: one zero bit each
@@ -283,27 +292,25 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const uint32_t* enc, uint32_t (
   uint32_t left = avail > 0 ? (uint32_t)avail : 0u;
   uint32_t r[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) r[i] = lead < 32 ? bitreverse(u[i] << lead) : 0u;  // bit t = plane (31-lead) - t
+  for (int i = 0; i < 4; ++i) r[i] = bitreverse(u[i] << (lead & 31u));  // bit t = plane (31-lead) - t; all zero if lead = 32
 #pragma unroll
   for (int j = 0; j < NW; ++j) W[j] = 0;
   uint32_t state = 0;  // byte offset of the current state's table rows
+  uint32_t planes = 0;
 #pragma unroll 1
-  for (int j = 0; j < 4; ++j) {
+  for (uint32_t step = 0; step < (uint32_t)kMaxSteps; ++step) {
     if (!any_lane_active(left > 0)) break;
-    uint32_t planes = gather_planes(r, j);
-#pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      uint32_t p = (planes >> (4 * m)) & 15u;
-      uint32_t e = enc[(state >> 2) + p];
-      uint32_t len = umin((e >> 8) & 7u, left);
-      shift_in<NW>(W, e & 0x7Fu, len);
-      left -= len;
-      state = e >> 16;
-    }
+    if ((step & 3u) == 0u) planes = gather_planes(r, step >> 2);
+    uint32_t two = (planes >> (8u * (step & 3u))) & 0xFFu;
+    uint32_t e = enc[(state >> 2) + two];
+    uint32_t len = umin((e >> 14) & 15u, left);
+    shift_in<NW>(W, e & 0x3FFFu, len);
+    left -= len;
+    state = e >> 18;
   }
-  // the first coded bit sits `coded` bits below the top; it belongs at bit 8 + lead
+  // the coded bits sit at the top of the window; the first belongs at bit 8 + lead
   shift_right<NW>(W, (uint32_t)(32 * NW - Traits<RATE>::kBlockBits) + left);
-  W[0] |= E & 0xFFu;
+  W[0] |= E;
 }
 
 // ---- inverse path ------------------------------------------------------------------
@@ -321,14 +328,13 @@ ZC_DEV void inverse_transform(const uint32_t (&u)[4], uint32_t E, float (&out)[4
   a = sub(a, c >> 1); c = add(c, a);
   c = sub(c, b >> 1); b = add(b, c);
   a = sub(a, d >> 1); d = add(d, a);
-  int ex = (int)E - 127 - kFractionBits;
-  int32_t q[4] = {a, b, c, d};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float v = (float)q[i];  // round to nearest even
-    v = __builtin_ldexpf(v, ex);  // exact scaling; rounds once more only for subnormals
-    out[i] = E ? v : 0.0f;
-  }
+  const int ex = (int)E - 127 - kFractionBits;
+  // int -> fp32 rounds to nearest even; the scaling is exact and rounds once more only
+  // for subnormal results.  A zero block arrives here with all words zero: +0.
+  out[0] = __builtin_ldexpf((float)a, ex);
+  out[1] = __builtin_ldexpf((float)b, ex);
+  out[2] = __builtin_ldexpf((float)c, ex);
+  out[3] = __builtin_ldexpf((float)d, ex);
 }
 
 // `dec` points at the decoder table.  W holds the block (bits beyond 4*RATE zero).
@@ -336,44 +342,55 @@ template <int RATE, class AnyActive>
 ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* dec, float (&out)[4],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
-  uint32_t E = W[0] & 0xFFu;
-  shift_out<NW>(W, 8);
-  // leading empty planes
+  constexpr int kPayload = Traits<RATE>::kPayloadBits;
+  constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
+  const uint32_t E = W[0] & 0xFFu;
+  // leading empty planes = zero bits at the start of the payload
   uint32_t lead = 0;
   {
     bool found = false;
 #pragma unroll
     for (int j = 0; j < NW; ++j) {
-      uint32_t z = count_trailing_zeros(W[j]);
+      uint32_t w = j == 0 ? (W[0] & 0xFFFFFF00u) : W[j];
+      uint32_t z = count_trailing_zeros(w);
       lead = found ? lead : lead + z;
-      found = found || (W[j] != 0);
+      found = found || (w != 0);
+    }
+    lead -= 8u;  // the header byte
+  }
+  lead = umin(lead, (uint32_t)kPayload);
+  uint32_t left = (uint32_t)kPayload - lead;
+  // a zero block ignores its payload; after 32 empty planes nothing is left to decode
+  if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
+  // keep the next stream bit at bit 2 of the window: bits 8..2 index the table directly
+  shift_right<NW>(W, lead + 6u);
+  uint32_t r[4] = {0, 0, 0, 0};
+  uint32_t state = 0, planes = 0;
+  uint32_t t = 0;
+#pragma unroll 1
+  for (; t < (uint32_t)kMaxPlanes; ++t) {
+    if (!any_lane_active(left > 0)) break;
+    uint32_t e = dec[((state + umin(left, 7u) * 512u) | (W[0] & 0x1FCu)) >> 2];
+    uint32_t len = (e >> 4) & 7u;
+    planes = alignbit(e, planes, 4);  // plane t's bits enter at the top
+    shift_out<NW>(W, len);
+    left -= len;
+    state = e >> 16;
+    if ((t & 7u) == 7u) {
+      uint32_t g = transpose_8x4(planes);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[i] |= ((g >> (8 * i)) & 0xFFu) << (t - 7u);
+      planes = 0;
     }
   }
-  lead = umin(lead, (uint32_t)Traits<RATE>::kPayloadBits);
-  uint32_t left = (uint32_t)Traits<RATE>::kPayloadBits - lead;
-  shift_right<NW>(W, umin(lead, 32u * NW - 1u));
-  uint32_t r[4] = {0, 0, 0, 0};
-  uint32_t state = 0;
-#pragma unroll 1
-  for (int j = 0; j < 4; ++j) {
-    if (!any_lane_active(left > 0)) break;
-    uint32_t planes = 0;
+  if ((t & 7u) != 0u) {  // a partly filled group of planes: bring plane (t & ~7) to nibble 0
+    uint32_t g = transpose_8x4(planes >> (4u * (8u - (t & 7u))));
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      uint32_t e = dec[(state >> 2) + umin(left, 7u) * 128u + (W[0] & 127u)];
-      uint32_t len = (e >> 4) & 7u;
-      planes |= (e & 15u) << (4 * m);
-      shift_out<NW>(W, len);
-      left -= len;
-      state = e >> 16;
-    }
-    uint32_t g = transpose_8x4(planes);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] |= ((g >> (8 * i)) & 0xFFu) << (8 * j);
+    for (int i = 0; i < 4; ++i) r[i] |= ((g >> (8 * i)) & 0xFFu) << (t & ~7u);
   }
   uint32_t u[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) u[i] = lead < 32 ? bitreverse(r[i]) >> lead : 0u;
+  for (int i = 0; i < 4; ++i) u[i] = bitreverse(r[i]) >> (lead & 31u);  // r is zero whenever lead >= 32
   inverse_transform(u, E, out);
 }
 

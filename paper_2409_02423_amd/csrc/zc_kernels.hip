@@ -19,7 +19,7 @@ __device__ const zc::DecTable g_dec_table = zc::build_dec_table();
 
 constexpr int kThreads = 256;          // 4 wavefronts
 constexpr int kWorkgroupsPerCU = 8;    // grid cap: resident workgroups, each loops
-constexpr int kEncWords = 5 * 16;
+constexpr int kEncWords = 5 * 256;
 constexpr int kDecWords = 5 * 8 * 128;
 constexpr int kMaxChunks = 16;
 
@@ -27,35 +27,49 @@ struct AnyLane {
   __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
 };
 
-__device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table, int words) {
-  for (int i = threadIdx.x; i < words; i += kThreads) lds[i] = table[i];
+// Copy a code table into LDS: every thread issues all of its 16-byte loads back to back.
+template <int WORDS>
+__device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table) {
+  static_assert(WORDS % 4 == 0, "table size");
+  constexpr int kVecs = WORDS / 4;
+  constexpr int kPerThread = (kVecs + kThreads - 1) / kThreads;
+  uint4 v[kPerThread];
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    int idx = threadIdx.x + i * kThreads;
+    v[i] = reinterpret_cast<const uint4*>(table)[idx < kVecs ? idx : 0];
+  }
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    int idx = threadIdx.x + i * kThreads;
+    if (idx < kVecs) reinterpret_cast<uint4*>(lds)[idx] = v[i];
+  }
 }
 
 // ---- block I/O ----------------------------------------------------------------------
 
-// Four values of block j as bit patterns; a ragged last block repeats the last value.
-__device__ __forceinline__ void load_values(const float* in, size_t n, size_t j, uint32_t (&x)[4]) {
-  if (4 * j + 4 <= n) {
-    uint4 v = reinterpret_cast<const uint4*>(in)[j];
-    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-  } else {
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(in);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      size_t idx = 4 * j + i;
-      x[i] = w[idx < n ? idx : n - 1];
-    }
-  }
+__device__ __forceinline__ void load_values(const float* in, size_t j, uint32_t (&x)[4]) {
+  uint4 v = reinterpret_cast<const uint4*>(in)[j];
+  x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
 }
 
-__device__ __forceinline__ void store_values(float* out, size_t n, size_t j, const float (&x)[4]) {
-  if (4 * j + 4 <= n) {
-    reinterpret_cast<float4*>(out)[j] = make_float4(x[0], x[1], x[2], x[3]);
-  } else {
+// The ragged last block (n % 4 values) repeats the last value.
+__device__ __forceinline__ void load_values_ragged(const float* in, size_t n, uint32_t (&x)[4]) {
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(in);
+  const size_t base = n & ~(size_t)3;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (4 * j + i < n) out[4 * j + i] = x[i];
-  }
+  for (int i = 0; i < 4; ++i) x[i] = w[base + i < n ? base + i : n - 1];
+}
+
+__device__ __forceinline__ void store_values(float* out, size_t j, const float (&x)[4]) {
+  reinterpret_cast<float4*>(out)[j] = make_float4(x[0], x[1], x[2], x[3]);
+}
+
+__device__ __forceinline__ void store_values_ragged(float* out, size_t n, const float (&x)[4]) {
+  const size_t base = n & ~(size_t)3;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (base + i < n) out[base + i] = x[i];
 }
 
 // Compressed block j: RATE/2 bytes at byte j*RATE/2; bits beyond the block are zero.
@@ -100,59 +114,79 @@ __device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint3
 }
 
 // ---- kernels ------------------------------------------------------------------------
+// Each kernel runs its lanes over the whole blocks with a grid stride, fetching the
+// next block (always an in-bounds address, so the loop body has no branch around the
+// load) before coding the current one; the ragged last block, if any, is left to one
+// lane at the end.
 
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restrict__ in, size_t n,
                                                             uint8_t* __restrict__ out) {
-  __shared__ uint32_t enc[kEncWords];
-  stage_table(enc, g_enc_table.v, kEncWords);
+  __shared__ __align__(16) uint32_t enc[kEncWords];
+  stage_table<kEncWords>(enc, g_enc_table.v);
   __syncthreads();
-  const size_t blocks = (n + 3) / 4;
+  constexpr int NW = zc::Traits<RATE>::kWords;
+  const size_t whole = n / 4;
   const size_t stride = (size_t)gridDim.x * kThreads;
   size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j >= blocks) return;
-  uint32_t x[4];
-  load_values(in, n, j, x);
-  while (true) {
-    const size_t jn = j + stride;
-    uint32_t xn[4] = {0, 0, 0, 0};
-    if (jn < blocks) load_values(in, n, jn, xn);
-    uint32_t W[zc::Traits<RATE>::kWords];
-    zc::encode_block<RATE>(x, enc, W, AnyLane());
-    store_stream<RATE>(out, j, W);
-    if (jn >= blocks) break;
+  if (j < whole) {
+    uint32_t x[4];
+    load_values(in, j, x);
+    while (true) {
+      const size_t jn = j + stride;
+      const bool more = jn < whole;
+      uint32_t xn[4];
+      load_values(in, more ? jn : j, xn);
+      uint32_t W[NW];
+      zc::encode_block<RATE>(x, enc, W, AnyLane());
+      store_stream<RATE>(out, j, W);
+      if (!more) break;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) x[i] = xn[i];
-    j = jn;
+      for (int i = 0; i < 4; ++i) x[i] = xn[i];
+      j = jn;
+    }
+  }
+  if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+    uint32_t x[4], W[NW];
+    load_values_ragged(in, n, x);
+    zc::encode_block<RATE>(x, enc, W, AnyLane());
+    store_stream<RATE>(out, whole, W);
   }
 }
 
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __restrict__ in, size_t n,
                                                               float* __restrict__ out) {
-  __shared__ uint32_t dec[kDecWords];
-  stage_table(dec, g_dec_table.v, kDecWords);
+  __shared__ __align__(16) uint32_t dec[kDecWords];
+  stage_table<kDecWords>(dec, g_dec_table.v);
   __syncthreads();
-  const size_t blocks = (n + 3) / 4;
+  constexpr int NW = zc::Traits<RATE>::kWords;
+  const size_t whole = n / 4;
   const size_t stride = (size_t)gridDim.x * kThreads;
   size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j >= blocks) return;
-  constexpr int NW = zc::Traits<RATE>::kWords;
-  uint32_t W[NW];
-  load_stream<RATE>(in, j, W);
-  while (true) {
-    const size_t jn = j + stride;
-    uint32_t Wn[NW];
+  if (j < whole) {
+    uint32_t W[NW];
+    load_stream<RATE>(in, j, W);
+    while (true) {
+      const size_t jn = j + stride;
+      const bool more = jn < whole;
+      uint32_t Wn[NW];
+      load_stream<RATE>(in, more ? jn : j, Wn);
+      float y[4];
+      zc::decode_block<RATE>(W, dec, y, AnyLane());
+      store_values(out, j, y);
+      if (!more) break;
 #pragma unroll
-    for (int i = 0; i < NW; ++i) Wn[i] = 0;
-    if (jn < blocks) load_stream<RATE>(in, jn, Wn);
+      for (int i = 0; i < NW; ++i) W[i] = Wn[i];
+      j = jn;
+    }
+  }
+  if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+    uint32_t W[NW];
     float y[4];
+    load_stream<RATE>(in, whole, W);
     zc::decode_block<RATE>(W, dec, y, AnyLane());
-    store_values(out, n, j, y);
-    if (jn >= blocks) break;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) W[i] = Wn[i];
-    j = jn;
+    store_values_ragged(out, n, y);
   }
 }
 
@@ -162,38 +196,65 @@ struct ChunkPointers {
 
 // Decode block j of every chunk, add in fp32 in chunk order, encode the sum.  The
 // output may be one of the inputs: a lane reads its block of all chunks before it
-// writes, and no other lane touches that block.
+// writes, and no other lane touches that block.  The blocks are visited in the order
+// (j, chunk 0), (j, chunk 1), ..., (j + stride, chunk 0), ... and the next one in that
+// order is fetched before the current one is decoded.
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, size_t n, uint8_t* out) {
-  __shared__ uint32_t dec[kDecWords];
-  __shared__ uint32_t enc[kEncWords];
-  stage_table(dec, g_dec_table.v, kDecWords);
-  stage_table(enc, g_enc_table.v, kEncWords);
+  __shared__ __align__(16) uint32_t dec[kDecWords];
+  __shared__ __align__(16) uint32_t enc[kEncWords];
+  stage_table<kDecWords>(dec, g_dec_table.v);
+  stage_table<kEncWords>(enc, g_enc_table.v);
   __syncthreads();
-  const size_t blocks = (n + 3) / 4;
-  const size_t stride = (size_t)gridDim.x * kThreads;
   constexpr int NW = zc::Traits<RATE>::kWords;
-  for (size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x; j < blocks; j += stride) {
+  const size_t whole = n / 4;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j < whole) {
+    uint32_t W[NW];
+    load_stream<RATE>(chunks.p[0], j, W);
+    while (true) {
+      const size_t jn = j + stride;
+      const bool more = jn < whole;
+      float s[4];
+      for (int c = 0; c < k; ++c) {
+        const bool last = c + 1 == k;
+        uint32_t Wn[NW];
+        load_stream<RATE>(chunks.p[last ? 0 : c + 1], last ? (more ? jn : j) : j, Wn);
+        float y[4];
+        zc::decode_block<RATE>(W, dec, y, AnyLane());
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
+#pragma unroll
+        for (int i = 0; i < NW; ++i) W[i] = Wn[i];
+      }
+      uint32_t x[4], Wo[NW];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[i]);
+      zc::encode_block<RATE>(x, enc, Wo, AnyLane());
+      store_stream<RATE>(out, j, Wo);
+      if (!more) break;
+      j = jn;
+    }
+  }
+  if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     float s[4] = {0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < k; ++c) {
       uint32_t W[NW];
-      load_stream<RATE>(chunks.p[c], j, W);
       float y[4];
+      load_stream<RATE>(chunks.p[c], whole, W);
       zc::decode_block<RATE>(W, dec, y, AnyLane());
 #pragma unroll
       for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
     }
-    uint32_t x[4];
+    // the result is compress(sum): the pad repeats the last valid sum
+    const int valid = (int)(n & 3);
+    const float pad = valid == 1 ? s[0] : (valid == 2 ? s[1] : s[2]);
+    uint32_t x[4], Wo[NW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // the result is compress(sum): pad lanes of a ragged last block repeat the last valid sum
-      size_t idx = 4 * j + i;
-      float v = idx < n ? s[i] : s[(n - 1) & 3];
-      x[i] = __float_as_uint(v);
-    }
-    uint32_t W[NW];
-    zc::encode_block<RATE>(x, enc, W, AnyLane());
-    store_stream<RATE>(out, j, W);
+    for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(i < valid ? s[i] : pad);
+    zc::encode_block<RATE>(x, enc, Wo, AnyLane());
+    store_stream<RATE>(out, whole, Wo);
   }
 }
 
