@@ -1,8 +1,8 @@
 // zc_codec.h -- per-block codec of libzc, as run by one GPU lane.
 //
 // One lane owns one block of 4 fp32 values.  The block's compressed form lives in
-// NW = ceil(4*RATE/32) registers; nothing here touches memory except the two
-// code tables, which the kernels stage in LDS.
+// NW = ceil(4*RATE/32) registers; nothing here touches memory except the code
+// tables, which the kernels stage in LDS.
 //
 // The paper names the codec family (ZFP, fixed rate; Sec. II-A, Sec. III-B) and its
 // rates (Sec. IV-C, IV-F) only; the stages implemented here are: shared exponent,
@@ -12,12 +12,15 @@
 //
 // How the bit-plane code is computed here (instead of bit by bit):
 //   * The state of the plane coder is only n in {0..4}, the number of leading
-//     coefficients already significant.  One plane's code word (at most 7 bits) is a
-//     function of (n, the plane's 4 bits): an 80-entry table.  Decoding one plane is
-//     a function of (n, bits left in the budget capped at 7, next 7 stream bits): a
-//     5*8*128-entry table that also resolves a code word cut short by the budget.
-//   * The four coefficient words are bit-transposed eight planes at a time (byte
-//     gather + four masked swaps), so a plane's 4 bits are one nibble.
+//     coefficients already significant.  The encoder looks up two planes at a time:
+//     (n, top two bits of each of the four coefficient words) -> code word of at most
+//     14 bits, its length and the next state.  The decoder looks up one plane at a
+//     time: (n, bits left in the budget capped at 7, next 7 stream bits) -> the
+//     plane's four bits, bits consumed, next state; this table also resolves a code
+//     word cut short by the budget.  At rate 4 the payload is a single byte and one
+//     256-entry table decodes it whole.
+//   * Coefficient words are consumed from the top by funnel shifts, and decoded plane
+//     bits are collected four byte lanes at a time, so no bit transposition is needed.
 //   * Empty leading planes cost one zero bit each and are skipped by a count of
 //     leading zeros (encoder) or trailing zeros of the payload (decoder).
 //   * The stream is built by shifting code words in at the top of a register window
@@ -48,64 +51,11 @@ ZC_DEV uint32_t alignbit(uint32_t hi, uint32_t lo, uint32_t s) {
 #endif
 }
 
-ZC_DEV uint32_t bitreverse(uint32_t x) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  return __builtin_bitreverse32(x);
-#else
-  x = ((x >> 1) & 0x55555555u) | ((x & 0x55555555u) << 1);
-  x = ((x >> 2) & 0x33333333u) | ((x & 0x33333333u) << 2);
-  x = ((x >> 4) & 0x0F0F0F0Fu) | ((x & 0x0F0F0F0Fu) << 4);
-  x = ((x >> 8) & 0x00FF00FFu) | ((x & 0x00FF00FFu) << 8);
-  return (x >> 16) | (x << 16);
-#endif
-}
-
 ZC_DEV uint32_t count_leading_zeros(uint32_t x) { return x ? (uint32_t)__builtin_clz(x) : 32u; }
 ZC_DEV uint32_t count_trailing_zeros(uint32_t x) { return x ? (uint32_t)__builtin_ctz(x) : 32u; }
 ZC_DEV uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 ZC_DEV uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
-
-// (x & ~mask) | (y & mask)
-ZC_DEV constexpr uint32_t bitselect(uint32_t mask, uint32_t y, uint32_t x) {
-  return (x & ~mask) | (y & mask);
-}
-
-// Exchange, for every position p in `low` (a mask), bit p with bit p + delta.
-ZC_DEV constexpr uint32_t swap_bit_groups(uint32_t x, uint32_t low, int delta) {
-  return bitselect(low << delta, x << delta, bitselect(low, x >> delta, x));
-}
-
-// A 32-bit word seen as 4 rows of 8 bits (bit 8*i + m) becomes 8 rows of 4 bits
-// (bit 4*m + i): four exchanges of two index bits each.
-ZC_DEV constexpr uint32_t transpose_4x8(uint32_t x) {
-  x = swap_bit_groups(x, 0x0000F0F0u, 12);
-  x = swap_bit_groups(x, 0x00CC00CCu, 6);
-  x = swap_bit_groups(x, 0x0A0A0A0Au, 3);
-  x = swap_bit_groups(x, 0x22222222u, 1);
-  return x;
-}
-ZC_DEV constexpr uint32_t transpose_8x4(uint32_t x) {
-  x = swap_bit_groups(x, 0x22222222u, 1);
-  x = swap_bit_groups(x, 0x0A0A0A0Au, 3);
-  x = swap_bit_groups(x, 0x00CC00CCu, 6);
-  x = swap_bit_groups(x, 0x0000F0F0u, 12);
-  return x;
-}
-
-namespace selfcheck {
-constexpr uint32_t naive_4x8(uint32_t x) {
-  uint32_t y = 0;
-  for (int i = 0; i < 4; ++i)
-    for (int m = 0; m < 8; ++m) y |= ((x >> (8 * i + m)) & 1u) << (4 * m + i);
-  return y;
-}
-static_assert(transpose_4x8(0x12345678u) == naive_4x8(0x12345678u), "transpose");
-static_assert(transpose_4x8(0xDEADBEEFu) == naive_4x8(0xDEADBEEFu), "transpose");
-static_assert(transpose_4x8(0x80000001u) == naive_4x8(0x80000001u), "transpose");
-static_assert(transpose_4x8(0x0F0055AAu) == naive_4x8(0x0F0055AAu), "transpose");
-static_assert(transpose_8x4(naive_4x8(0xC001D00Du)) == 0xC001D00Du, "transpose back");
-static_assert(transpose_8x4(transpose_4x8(0x7E57AB1Eu)) == 0x7E57AB1Eu, "transpose back");
-}  // namespace selfcheck
+ZC_DEV float bits_to_float(uint32_t b) { return __builtin_bit_cast(float, b); }
 
 // ---- code tables -------------------------------------------------------------------
 
@@ -134,28 +84,58 @@ constexpr PlaneCode code_one_plane(int n, int p) {
   return PlaneCode{code, len, i};
 }
 
-// Encoder, two planes per step: entry[n*256 + (second plane << 4 | first plane)] =
-// code word (<= 14 bits) | length << 14 | (byte offset of the next state's 256
-// entries) << 18.
+// The reverse: read one plane in state n from the low bits of `s`, of which only
+// `avail` are inside the budget.  A group known to hold a one that the budget cut
+// before it was located gets the one at the lowest index still possible.
+struct PlaneBits { uint32_t p; int used; int next; };
+
+constexpr PlaneBits read_one_plane(int n, int avail, uint32_t s) {
+  int left = avail, pos = 0;
+  uint32_t p = 0;
+  for (int i = 0; i < n && left > 0; ++i, --left) p |= ((s >> pos++) & 1u) << i;
+  int i = n;
+  while (i < 4 && left > 0) {
+    int any = (int)((s >> pos++) & 1u);
+    --left;
+    if (!any) break;
+    while (i < 3 && left > 0) {
+      int b = (int)((s >> pos++) & 1u);
+      --left;
+      if (b) break;
+      ++i;
+    }
+    p |= 1u << i;
+    ++i;
+  }
+  return PlaneBits{p, pos, i};
+}
+
+// Encoder, two planes per step.  Index = n*256 + x, where bits 7:6 of x are the next
+// two planes of coefficient 0 (earlier plane in the higher bit), 5:4 of coefficient 1,
+// 3:2 of coefficient 2, 1:0 of coefficient 3.  Entry = code word (bits 13:0) |
+// length << 14 | (byte offset of the next state's 256 entries) << 18.
 struct EncTable { uint32_t v[5 * 256]; };
 
 constexpr EncTable build_enc_table() {
   EncTable t{};
   for (int n = 0; n <= 4; ++n)
-    for (int pp = 0; pp < 256; ++pp) {
-      PlaneCode a = code_one_plane(n, pp & 15);
-      PlaneCode b = code_one_plane(a.next, pp >> 4);
-      t.v[n * 256 + pp] = (a.code | b.code << a.len) | (uint32_t)(a.len + b.len) << 14 |
-                          (uint32_t)(b.next * 256 * 4) << 18;
+    for (int x = 0; x < 256; ++x) {
+      int first = 0, second = 0;
+      for (int i = 0; i < 4; ++i) {
+        first |= ((x >> (7 - 2 * i)) & 1) << i;
+        second |= ((x >> (6 - 2 * i)) & 1) << i;
+      }
+      PlaneCode a = code_one_plane(n, first);
+      PlaneCode b = code_one_plane(a.next, second);
+      t.v[n * 256 + x] = (a.code | b.code << a.len) | (uint32_t)(a.len + b.len) << 14 |
+                         (uint32_t)(b.next * 256 * 4) << 18;
     }
   return t;
 }
 
-// Decoder, one plane per step: entry[(n*8 + min(bits left, 7))*128 + next 7 stream
-// bits] = plane bits | bits consumed << 4 | (byte offset of the next state's 8*128
-// entries) << 16.  With fewer than 7 bits left the stream bits beyond the budget are
-// ignored, and a group known to hold a one that the budget cut before it was located
-// gets the one at the lowest index still possible.
+// Decoder, one plane per step.  Index = (n*8 + min(bits left, 7))*128 + next 7 stream
+// bits.  Entry = the plane's bit of coefficient i at bit 8*i | bits consumed << 1 |
+// (next state) << 12, which is the byte offset of that state's 8*128 entries.
 struct DecTable { uint32_t v[5 * 8 * 128]; };
 
 constexpr DecTable build_dec_table() {
@@ -163,27 +143,41 @@ constexpr DecTable build_dec_table() {
   for (int n = 0; n <= 4; ++n)
     for (int avail = 0; avail < 8; ++avail)
       for (int s = 0; s < 128; ++s) {
-        int left = avail, pos = 0;
-        uint32_t p = 0;
-        for (int i = 0; i < n && left > 0; ++i, --left) p |= (uint32_t)((s >> pos++) & 1) << i;
-        int i = n;
-        while (i < 4 && left > 0) {
-          int any = (s >> pos++) & 1;
-          --left;
-          if (!any) break;
-          while (i < 3 && left > 0) {
-            int b = (s >> pos++) & 1;
-            --left;
-            if (b) break;
-            ++i;
-          }
-          p |= 1u << i;
-          ++i;
-        }
-        t.v[(n * 8 + avail) * 128 + s] = p | (uint32_t)pos << 4 | (uint32_t)(i * 8 * 128 * 4) << 16;
+        PlaneBits r = read_one_plane(n, avail, (uint32_t)s);
+        uint32_t spread = (r.p & 1u) | (r.p & 2u) << 7 | (r.p & 4u) << 14 | (r.p & 8u) << 21;
+        t.v[(n * 8 + avail) * 128 + s] = spread | (uint32_t)r.used << 1 | (uint32_t)r.next << 12;
       }
   return t;
 }
+
+// Rate 4: the whole 8-bit payload -> top byte of each coefficient word (coefficient i
+// in byte i).  Eight payload bits reach at most planes 31..24.
+struct Dec8Table { uint32_t v[256]; };
+
+constexpr Dec8Table build_dec8_table() {
+  Dec8Table t{};
+  for (uint32_t payload = 0; payload < 256; ++payload) {
+    uint32_t u[4] = {0, 0, 0, 0};
+    int left = 8, n = 0;
+    uint32_t s = payload;
+    for (int k = 31; k >= 24 && left > 0; --k) {
+      PlaneBits r = read_one_plane(n, left, s);
+      for (int i = 0; i < 4; ++i) u[i] |= ((r.p >> i) & 1u) << k;
+      s >>= r.used;
+      left -= r.used;
+      n = r.next;
+    }
+    t.v[payload] = (u[0] >> 24) | (u[1] >> 24) << 8 | (u[2] >> 24) << 16 | (u[3] >> 24) << 24;
+  }
+  return t;
+}
+
+// Pointers to the staged tables; a kernel sets only those its rate uses.
+struct Tables {
+  const uint32_t* enc;
+  const uint32_t* dec;
+  const uint32_t* dec8;
+};
 
 // ---- register window holding one compressed block ----------------------------------
 
@@ -239,8 +233,6 @@ ZC_DEV void shift_out(uint32_t (&W)[NW], uint32_t len) {
 
 // ---- forward path ------------------------------------------------------------------
 
-ZC_DEV float bits_to_float(uint32_t b) { return __builtin_bit_cast(float, b); }
-
 // Four fp32 bit patterns -> biased block exponent E and the four negabinary
 // coefficient words.  With m the largest magnitude as a bit pattern, E = (exponent
 // field of m) + (m != 0): field + 1 for a normal maximum, 1 for a subnormal-only
@@ -266,19 +258,11 @@ ZC_DEV void forward_transform(const uint32_t (&x)[4], uint32_t& E, uint32_t (&u)
   u[3] = ((uint32_t)d + 0xAAAAAAAAu) ^ 0xAAAAAAAAu;
 }
 
-// Byte `j` of each of four words, packed (word i -> byte i), then transposed so that
-// nibble m holds bit 8*j + m of the four words.
-ZC_DEV uint32_t gather_planes(const uint32_t (&r)[4], uint32_t j) {
-  uint32_t g = ((r[0] >> (8 * j)) & 0xFFu) | (((r[1] >> (8 * j)) & 0xFFu) << 8) |
-               (((r[2] >> (8 * j)) & 0xFFu) << 16) | (((r[3] >> (8 * j)) & 0xFFu) << 24);
-  return transpose_4x8(g);
-}
-
 // Whole block: exponent byte + embedded code of the coefficients, cut at the budget.
-// `enc` points at the encoder table (LDS on the GPU).  `any_lane_active(pred)` tells
-// whether any lane of the wavefront still has pred set (loop control only).
+// `any_lane_active(pred)` tells whether any lane of the wavefront still has pred set
+// (loop control only).
 template <int RATE, class AnyActive>
-ZC_DEV void encode_block(const uint32_t (&x)[4], const uint32_t* enc, uint32_t (&W)[Traits<RATE>::kWords],
+ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W)[Traits<RATE>::kWords],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
   // every plane costs at least one bit, so at most this many planes are ever coded
@@ -287,24 +271,26 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const uint32_t* enc, uint32_t (
   uint32_t E, u[4];
   forward_transform(x, E, u);
   // leading empty planes: one zero bit each
-  uint32_t lead = count_leading_zeros(u[0] | u[1] | u[2] | u[3]);
-  int32_t avail = Traits<RATE>::kPayloadBits - (int32_t)lead;
+  const uint32_t lead = count_leading_zeros(u[0] | u[1] | u[2] | u[3]);
+  const int32_t avail = Traits<RATE>::kPayloadBits - (int32_t)lead;
   uint32_t left = avail > 0 ? (uint32_t)avail : 0u;
-  uint32_t r[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) r[i] = bitreverse(u[i] << (lead & 31u));  // bit t = plane (31-lead) - t; all zero if lead = 32
+  for (int i = 0; i < 4; ++i) u[i] <<= (lead & 31u);  // top plane to bit 31 (all words are zero if lead = 32)
 #pragma unroll
   for (int j = 0; j < NW; ++j) W[j] = 0;
   uint32_t state = 0;  // byte offset of the current state's table rows
-  uint32_t planes = 0;
 #pragma unroll 1
-  for (uint32_t step = 0; step < (uint32_t)kMaxSteps; ++step) {
+  for (int step = 0; step < kMaxSteps; ++step) {
     if (!any_lane_active(left > 0)) break;
-    if ((step & 3u) == 0u) planes = gather_planes(r, step >> 2);
-    uint32_t two = (planes >> (8u * (step & 3u))) & 0xFFu;
-    uint32_t e = enc[(state >> 2) + two];
-    uint32_t len = umin((e >> 14) & 15u, left);
-    shift_in<NW>(W, e & 0x3FFFu, len);
+    uint32_t idx = u[0] >> 30;
+    idx = alignbit(idx, u[1], 30);  // (idx << 2) | top two bits of the next word
+    idx = alignbit(idx, u[2], 30);
+    idx = alignbit(idx, u[3], 30);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) u[i] <<= 2;
+    const uint32_t e = tab.enc[(state >> 2) + idx];
+    const uint32_t len = umin((e >> 14) & 15u, left);
+    shift_in<NW>(W, e, len);  // only the low `len` bits of e enter the window
     left -= len;
     state = e >> 18;
   }
@@ -337,60 +323,74 @@ ZC_DEV void inverse_transform(const uint32_t (&u)[4], uint32_t E, float (&out)[4
   out[3] = __builtin_ldexpf((float)d, ex);
 }
 
-// `dec` points at the decoder table.  W holds the block (bits beyond 4*RATE zero).
+// W holds the block (bits beyond 4*RATE zero).
 template <int RATE, class AnyActive>
-ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* dec, float (&out)[4],
+ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab, float (&out)[4],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
   constexpr int kPayload = Traits<RATE>::kPayloadBits;
-  constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
   const uint32_t E = W[0] & 0xFFu;
-  // leading empty planes = zero bits at the start of the payload
-  uint32_t lead = 0;
-  {
-    bool found = false;
-#pragma unroll
-    for (int j = 0; j < NW; ++j) {
-      uint32_t w = j == 0 ? (W[0] & 0xFFFFFF00u) : W[j];
-      uint32_t z = count_trailing_zeros(w);
-      lead = found ? lead : lead + z;
-      found = found || (w != 0);
-    }
-    lead -= 8u;  // the header byte
-  }
-  lead = umin(lead, (uint32_t)kPayload);
-  uint32_t left = (uint32_t)kPayload - lead;
-  // a zero block ignores its payload; after 32 empty planes nothing is left to decode
-  if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
-  // keep the next stream bit at bit 2 of the window: bits 8..2 index the table directly
-  shift_right<NW>(W, lead + 6u);
-  uint32_t r[4] = {0, 0, 0, 0};
-  uint32_t state = 0, planes = 0;
-  uint32_t t = 0;
-#pragma unroll 1
-  for (; t < (uint32_t)kMaxPlanes; ++t) {
-    if (!any_lane_active(left > 0)) break;
-    uint32_t e = dec[((state + umin(left, 7u) * 512u) | (W[0] & 0x1FCu)) >> 2];
-    uint32_t len = (e >> 4) & 7u;
-    planes = alignbit(e, planes, 4);  // plane t's bits enter at the top
-    shift_out<NW>(W, len);
-    left -= len;
-    state = e >> 16;
-    if ((t & 7u) == 7u) {
-      uint32_t g = transpose_8x4(planes);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] |= ((g >> (8 * i)) & 0xFFu) << (t - 7u);
-      planes = 0;
-    }
-  }
-  if ((t & 7u) != 0u) {  // a partly filled group of planes: bring plane (t & ~7) to nibble 0
-    uint32_t g = transpose_8x4(planes >> (4u * (8u - (t & 7u))));
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] |= ((g >> (8 * i)) & 0xFFu) << (t & ~7u);
-  }
   uint32_t u[4];
+  if constexpr (RATE == 4) {
+    // one lookup for the whole payload byte; a zero block ignores its payload
+    const uint32_t top = E ? tab.dec8[W[0] >> 8] : 0u;
+    u[0] = top << 24;
+    u[1] = (top << 16) & 0xFF000000u;
+    u[2] = (top << 8) & 0xFF000000u;
+    u[3] = top & 0xFF000000u;
+  } else {
+    constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
+    constexpr int kGroups = (kMaxPlanes + 7) / 8;
+    // leading empty planes = zero bits at the start of the payload
+    uint32_t lead = 0;
+    {
+      bool found = false;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) u[i] = bitreverse(r[i]) >> (lead & 31u);  // r is zero whenever lead >= 32
+      for (int j = 0; j < NW; ++j) {
+        const uint32_t w = j == 0 ? (W[0] & 0xFFFFFF00u) : W[j];
+        const uint32_t z = count_trailing_zeros(w);
+        lead = found ? lead : lead + z;
+        found = found || (w != 0);
+      }
+      lead -= 8u;  // the header byte
+    }
+    lead = umin(lead, (uint32_t)kPayload);
+    uint32_t left = (uint32_t)kPayload - lead;
+    // a zero block ignores its payload; after 32 empty planes nothing is left to decode
+    if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
+    // keep the next stream bit at bit 2 of the window: bits 8..2 index the table directly
+    shift_right<NW>(W, lead + 6u);
+    uint32_t state = 0;
+    uint32_t G[kGroups];  // G[g]: byte i = planes 8g..8g+7 (from the top) of coefficient i, first plane in bit 7
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) G[g] = 0;
+    bool open = true;
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+      if (open) {
+        uint32_t acc = 0, m = 0;
+#pragma unroll 1
+        for (; m < 8u; ++m) {
+          if (!any_lane_active(left > 0)) break;
+          const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
+          const uint32_t len = (e >> 1) & 7u;
+          acc = (acc << 1) | (e & 0x01010101u);
+          shift_out<NW>(W, len);
+          left -= len;
+          state = e & 0x7000u;
+        }
+        G[g] = acc << (8u - m);
+        open = m == 8u;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t v = 0;
+#pragma unroll
+      for (int g = 0; g < kGroups; ++g) v |= ((G[g] >> (8 * i)) & 0xFFu) << (24 - 8 * g);
+      u[i] = v >> (lead & 31u);  // nothing was decoded if lead >= 32
+    }
+  }
   inverse_transform(u, E, out);
 }
 

@@ -16,11 +16,13 @@ namespace {
 
 __device__ const zc::EncTable g_enc_table = zc::build_enc_table();
 __device__ const zc::DecTable g_dec_table = zc::build_dec_table();
+__device__ const zc::Dec8Table g_dec8_table = zc::build_dec8_table();
 
 constexpr int kThreads = 256;          // 4 wavefronts
 constexpr int kWorkgroupsPerCU = 8;    // grid cap: resident workgroups, each loops
 constexpr int kEncWords = 5 * 256;
 constexpr int kDecWords = 5 * 8 * 128;
+constexpr int kDec8Words = 256;
 constexpr int kMaxChunks = 16;
 
 struct AnyLane {
@@ -43,6 +45,22 @@ __device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table
   for (int i = 0; i < kPerThread; ++i) {
     int idx = threadIdx.x + i * kThreads;
     if (idx < kVecs) reinterpret_cast<uint4*>(lds)[idx] = v[i];
+  }
+}
+
+// Rate 4 decodes its one payload byte with the 256-entry table; the other rates use the
+// per-plane table.
+template <int RATE>
+constexpr int decoder_table_words() { return RATE == 4 ? kDec8Words : kDecWords; }
+
+template <int RATE>
+__device__ __forceinline__ zc::Tables stage_decoder_table(uint32_t* lds, const uint32_t* enc) {
+  if constexpr (RATE == 4) {
+    stage_table<kDec8Words>(lds, g_dec8_table.v);
+    return zc::Tables{enc, nullptr, lds};
+  } else {
+    stage_table<kDecWords>(lds, g_dec_table.v);
+    return zc::Tables{enc, lds, nullptr};
   }
 }
 
@@ -125,6 +143,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
   __shared__ __align__(16) uint32_t enc[kEncWords];
   stage_table<kEncWords>(enc, g_enc_table.v);
   __syncthreads();
+  const zc::Tables tab = {enc, nullptr, nullptr};
   constexpr int NW = zc::Traits<RATE>::kWords;
   const size_t whole = n / 4;
   const size_t stride = (size_t)gridDim.x * kThreads;
@@ -138,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
       uint32_t xn[4];
       load_values(in, more ? jn : j, xn);
       uint32_t W[NW];
-      zc::encode_block<RATE>(x, enc, W, AnyLane());
+      zc::encode_block<RATE>(x, tab, W, AnyLane());
       store_stream<RATE>(out, j, W);
       if (!more) break;
 #pragma unroll
@@ -149,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t x[4], W[NW];
     load_values_ragged(in, n, x);
-    zc::encode_block<RATE>(x, enc, W, AnyLane());
+    zc::encode_block<RATE>(x, tab, W, AnyLane());
     store_stream<RATE>(out, whole, W);
   }
 }
@@ -157,8 +176,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __restrict__ in, size_t n,
                                                               float* __restrict__ out) {
-  __shared__ __align__(16) uint32_t dec[kDecWords];
-  stage_table<kDecWords>(dec, g_dec_table.v);
+  __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
+  const zc::Tables tab = stage_decoder_table<RATE>(dec, nullptr);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;
   const size_t whole = n / 4;
@@ -173,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
       uint32_t Wn[NW];
       load_stream<RATE>(in, more ? jn : j, Wn);
       float y[4];
-      zc::decode_block<RATE>(W, dec, y, AnyLane());
+      zc::decode_block<RATE>(W, tab, y, AnyLane());
       store_values(out, j, y);
       if (!more) break;
 #pragma unroll
@@ -185,7 +204,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
     uint32_t W[NW];
     float y[4];
     load_stream<RATE>(in, whole, W);
-    zc::decode_block<RATE>(W, dec, y, AnyLane());
+    zc::decode_block<RATE>(W, tab, y, AnyLane());
     store_values_ragged(out, n, y);
   }
 }
@@ -201,10 +220,10 @@ struct ChunkPointers {
 // order is fetched before the current one is decoded.
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, size_t n, uint8_t* out) {
-  __shared__ __align__(16) uint32_t dec[kDecWords];
+  __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
   __shared__ __align__(16) uint32_t enc[kEncWords];
-  stage_table<kDecWords>(dec, g_dec_table.v);
   stage_table<kEncWords>(enc, g_enc_table.v);
+  const zc::Tables tab = stage_decoder_table<RATE>(dec, enc);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;
   const size_t whole = n / 4;
@@ -222,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
         uint32_t Wn[NW];
         load_stream<RATE>(chunks.p[last ? 0 : c + 1], last ? (more ? jn : j) : j, Wn);
         float y[4];
-        zc::decode_block<RATE>(W, dec, y, AnyLane());
+        zc::decode_block<RATE>(W, tab, y, AnyLane());
 #pragma unroll
         for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
 #pragma unroll
@@ -231,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
       uint32_t x[4], Wo[NW];
 #pragma unroll
       for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[i]);
-      zc::encode_block<RATE>(x, enc, Wo, AnyLane());
+      zc::encode_block<RATE>(x, tab, Wo, AnyLane());
       store_stream<RATE>(out, j, Wo);
       if (!more) break;
       j = jn;
@@ -243,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
       uint32_t W[NW];
       float y[4];
       load_stream<RATE>(chunks.p[c], whole, W);
-      zc::decode_block<RATE>(W, dec, y, AnyLane());
+      zc::decode_block<RATE>(W, tab, y, AnyLane());
 #pragma unroll
       for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
     }
@@ -253,7 +272,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
     uint32_t x[4], Wo[NW];
 #pragma unroll
     for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(i < valid ? s[i] : pad);
-    zc::encode_block<RATE>(x, enc, Wo, AnyLane());
+    zc::encode_block<RATE>(x, tab, Wo, AnyLane());
     store_stream<RATE>(out, whole, Wo);
   }
 }

@@ -8,13 +8,15 @@
 namespace {
 const zc::EncTable kEnc = zc::build_enc_table();
 const zc::DecTable kDec = zc::build_dec_table();
+const zc::Dec8Table kDec8 = zc::build_dec8_table();
+const zc::Tables kTables = {kEnc.v, kDec.v, kDec8.v};
 auto always = [](bool p) { return p; };
 
 template <int RATE>
 void enc(const float* x, uint8_t* out) {
   uint32_t b[4], W[zc::Traits<RATE>::kWords];
   std::memcpy(b, x, 16);
-  zc::encode_block<RATE>(b, kEnc.v, W, always);
+  zc::encode_block<RATE>(b, kTables, W, always);
   std::memcpy(out, W, zc::Traits<RATE>::kBlockBytes);
 }
 template <int RATE>
@@ -22,7 +24,7 @@ void dec(const uint8_t* in, float* x) {
   uint32_t W[zc::Traits<RATE>::kWords] = {};
   std::memcpy(W, in, zc::Traits<RATE>::kBlockBytes);
   float o[4];
-  zc::decode_block<RATE>(W, kDec.v, o, always);
+  zc::decode_block<RATE>(W, kTables, o, always);
   std::memcpy(x, o, 16);
 }
 }  // namespace
