@@ -18,7 +18,7 @@
 //     time: (n, bits left in the budget capped at 7, next 7 stream bits) -> the
 //     plane's four bits, bits consumed, next state; this table also resolves a code
 //     word cut short by the budget.  At rate 4 the payload is a single byte and one
-//     256-entry table decodes it whole.
+//     256-entry table holds the decoded block up to its power-of-two scale.
 //   * Coefficient words are consumed from the top by funnel shifts, and decoded plane
 //     bits are collected four byte lanes at a time, so no bit transposition is needed.
 //   * Empty leading planes cost one zero bit each and are skipped by a count of
@@ -150,12 +150,28 @@ constexpr DecTable build_dec_table() {
   return t;
 }
 
-// Rate 4: the whole 8-bit payload -> top byte of each coefficient word (coefficient i
-// in byte i).  Eight payload bits reach at most planes 31..24.
-struct Dec8Table { uint32_t v[256]; };
+// Inverse of the lifting steps (wrap-around arithmetic, arithmetic shifts).
+constexpr void inverse_lift(int32_t& a, int32_t& b, int32_t& c, int32_t& d) {
+  auto add = [](int32_t p, int32_t q) { return (int32_t)((uint32_t)p + (uint32_t)q); };
+  auto sub = [](int32_t p, int32_t q) { return (int32_t)((uint32_t)p - (uint32_t)q); };
+  b = add(b, d); d = sub(d, b >> 2);
+  d = sub(d, b >> 1); b = add(b, d);
+  a = sub(a, c >> 1); c = add(c, a);
+  c = sub(c, b >> 1); b = add(b, c);
+  a = sub(a, d >> 1); d = add(d, a);
+}
 
-constexpr Dec8Table build_dec8_table() {
-  Dec8Table t{};
+constexpr int32_t from_negabinary(uint32_t u) { return (int32_t)((u ^ 0xAAAAAAAAu) - 0xAAAAAAAAu); }
+
+// Rate 4: the payload is one byte, so everything between the header and the final
+// scaling is a function of 256 cases.  Entry = the four fixed-point values of the
+// block as floats (4 floats per payload value); they are multiples of 2^22 below
+// 2^31 in magnitude, hence exact in fp32.  Eight payload bits reach at most planes
+// 31..24 of the coefficient words.
+struct Dec4Table { float v[256 * 4]; };
+
+constexpr Dec4Table build_dec4_table() {
+  Dec4Table t{};
   for (uint32_t payload = 0; payload < 256; ++payload) {
     uint32_t u[4] = {0, 0, 0, 0};
     int left = 8, n = 0;
@@ -167,7 +183,12 @@ constexpr Dec8Table build_dec8_table() {
       left -= r.used;
       n = r.next;
     }
-    t.v[payload] = (u[0] >> 24) | (u[1] >> 24) << 8 | (u[2] >> 24) << 16 | (u[3] >> 24) << 24;
+    int32_t a = from_negabinary(u[0]), b = from_negabinary(u[1]), c = from_negabinary(u[2]), d = from_negabinary(u[3]);
+    inverse_lift(a, b, c, d);
+    t.v[4 * payload + 0] = (float)a;
+    t.v[4 * payload + 1] = (float)b;
+    t.v[4 * payload + 2] = (float)c;
+    t.v[4 * payload + 3] = (float)d;
   }
   return t;
 }
@@ -176,7 +197,7 @@ constexpr Dec8Table build_dec8_table() {
 struct Tables {
   const uint32_t* enc;
   const uint32_t* dec;
-  const uint32_t* dec8;
+  const float* dec4;
 };
 
 // ---- register window holding one compressed block ----------------------------------
@@ -302,18 +323,8 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
 // ---- inverse path ------------------------------------------------------------------
 
 ZC_DEV void inverse_transform(const uint32_t (&u)[4], uint32_t E, float (&out)[4]) {
-  int32_t a = (int32_t)((u[0] ^ 0xAAAAAAAAu) - 0xAAAAAAAAu);
-  int32_t b = (int32_t)((u[1] ^ 0xAAAAAAAAu) - 0xAAAAAAAAu);
-  int32_t c = (int32_t)((u[2] ^ 0xAAAAAAAAu) - 0xAAAAAAAAu);
-  int32_t d = (int32_t)((u[3] ^ 0xAAAAAAAAu) - 0xAAAAAAAAu);
-  // wrap-around is part of the format: unsigned adds, arithmetic shifts
-  auto add = [](int32_t p, int32_t q) { return (int32_t)((uint32_t)p + (uint32_t)q); };
-  auto sub = [](int32_t p, int32_t q) { return (int32_t)((uint32_t)p - (uint32_t)q); };
-  b = add(b, d); d = sub(d, b >> 2);
-  d = sub(d, b >> 1); b = add(b, d);
-  a = sub(a, c >> 1); c = add(c, a);
-  c = sub(c, b >> 1); b = add(b, c);
-  a = sub(a, d >> 1); d = add(d, a);
+  int32_t a = from_negabinary(u[0]), b = from_negabinary(u[1]), c = from_negabinary(u[2]), d = from_negabinary(u[3]);
+  inverse_lift(a, b, c, d);
   const int ex = (int)E - 127 - kFractionBits;
   // int -> fp32 rounds to nearest even; the scaling is exact and rounds once more only
   // for subnormal results.  A zero block arrives here with all words zero: +0.
@@ -330,15 +341,15 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
   constexpr int NW = Traits<RATE>::kWords;
   constexpr int kPayload = Traits<RATE>::kPayloadBits;
   const uint32_t E = W[0] & 0xFFu;
-  uint32_t u[4];
   if constexpr (RATE == 4) {
-    // one lookup for the whole payload byte; a zero block ignores its payload
-    const uint32_t top = E ? tab.dec8[W[0] >> 8] : 0u;
-    u[0] = top << 24;
-    u[1] = (top << 16) & 0xFF000000u;
-    u[2] = (top << 8) & 0xFF000000u;
-    u[3] = top & 0xFF000000u;
+    // one lookup for the whole payload byte (entry 0 is the zero block, which ignores
+    // its payload), then only the scaling by 2^(E - 155) is left
+    const float* q = tab.dec4 + 4u * (E ? W[0] >> 8 : 0u);
+    const int ex = (int)E - 127 - kFractionBits;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = __builtin_ldexpf(q[i], ex);
   } else {
+    uint32_t u[4];
     constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
     constexpr int kGroups = (kMaxPlanes + 7) / 8;
     // leading empty planes = zero bits at the start of the payload
@@ -390,8 +401,8 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
       for (int g = 0; g < kGroups; ++g) v |= ((G[g] >> (8 * i)) & 0xFFu) << (24 - 8 * g);
       u[i] = v >> (lead & 31u);  // nothing was decoded if lead >= 32
     }
+    inverse_transform(u, E, out);
   }
-  inverse_transform(u, E, out);
 }
 
 }  // namespace zc

@@ -8,6 +8,7 @@
 // coded.  No matrix cores: nothing here is a contraction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/zc.h"
 #include "zc_codec.h"
@@ -16,13 +17,12 @@ namespace {
 
 __device__ const zc::EncTable g_enc_table = zc::build_enc_table();
 __device__ const zc::DecTable g_dec_table = zc::build_dec_table();
-__device__ const zc::Dec8Table g_dec8_table = zc::build_dec8_table();
+__device__ const zc::Dec4Table g_dec4_table = zc::build_dec4_table();
 
 constexpr int kThreads = 256;          // 4 wavefronts
-constexpr int kWorkgroupsPerCU = 8;    // grid cap: resident workgroups, each loops
 constexpr int kEncWords = 5 * 256;
 constexpr int kDecWords = 5 * 8 * 128;
-constexpr int kDec8Words = 256;
+constexpr int kDec4Words = 256 * 4;
 constexpr int kMaxChunks = 16;
 
 struct AnyLane {
@@ -48,16 +48,16 @@ __device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table
   }
 }
 
-// Rate 4 decodes its one payload byte with the 256-entry table; the other rates use the
-// per-plane table.
+// Rate 4 decodes its one payload byte with the 256-entry block table; the other rates
+// use the per-plane table.
 template <int RATE>
-constexpr int decoder_table_words() { return RATE == 4 ? kDec8Words : kDecWords; }
+constexpr int decoder_table_words() { return RATE == 4 ? kDec4Words : kDecWords; }
 
 template <int RATE>
 __device__ __forceinline__ zc::Tables stage_decoder_table(uint32_t* lds, const uint32_t* enc) {
   if constexpr (RATE == 4) {
-    stage_table<kDec8Words>(lds, g_dec8_table.v);
-    return zc::Tables{enc, nullptr, lds};
+    stage_table<kDec4Words>(lds, reinterpret_cast<const uint32_t*>(g_dec4_table.v));
+    return zc::Tables{enc, nullptr, reinterpret_cast<const float*>(lds)};
   } else {
     stage_table<kDecWords>(lds, g_dec_table.v);
     return zc::Tables{enc, lds, nullptr};
@@ -66,8 +66,22 @@ __device__ __forceinline__ zc::Tables stage_decoder_table(uint32_t* lds, const u
 
 // ---- block I/O ----------------------------------------------------------------------
 
+// Message buffers are streamed once.  Measured on MI355X: non-temporal 16-byte fp32
+// loads and stores are faster than plain ones (the decompress kernel's 1 GiB of
+// output by a third), non-temporal stores of the narrow stream are no slower, but
+// non-temporal loads of the narrow stream are slower than plain ones.  So: fp32 in
+// and out and stream out are non-temporal, stream in is plain.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <class T>
+__device__ __forceinline__ T nt_load(const T* p) { return __builtin_nontemporal_load(p); }
+
+template <class T>
+__device__ __forceinline__ void nt_store(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
 __device__ __forceinline__ void load_values(const float* in, size_t j, uint32_t (&x)[4]) {
-  uint4 v = reinterpret_cast<const uint4*>(in)[j];
+  u32x4 v = nt_load(reinterpret_cast<const u32x4*>(in) + j);
   x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
 }
 
@@ -80,7 +94,8 @@ __device__ __forceinline__ void load_values_ragged(const float* in, size_t n, ui
 }
 
 __device__ __forceinline__ void store_values(float* out, size_t j, const float (&x)[4]) {
-  reinterpret_cast<float4*>(out)[j] = make_float4(x[0], x[1], x[2], x[3]);
+  u32x4 v = {__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+  nt_store(reinterpret_cast<u32x4*>(out) + j, v);
 }
 
 __device__ __forceinline__ void store_values_ragged(float* out, size_t n, const float (&x)[4]) {
@@ -96,10 +111,10 @@ __device__ __forceinline__ void load_stream(const uint8_t* in, size_t j, uint32_
   constexpr int B = zc::Traits<RATE>::kBlockBytes;
   const uint8_t* p = in + j * B;
   if constexpr (B == 16) {
-    uint4 v = *reinterpret_cast<const uint4*>(p);
+    u32x4 v = *reinterpret_cast<const u32x4*>(p);
     W[0] = v.x; W[1] = v.y; W[2] = v.z; W[3] = v.w;
   } else if constexpr (B == 8) {
-    uint2 v = *reinterpret_cast<const uint2*>(p);
+    u32x2 v = *reinterpret_cast<const u32x2*>(p);
     W[0] = v.x; W[1] = v.y;
   } else if constexpr (B % 4 == 0) {
 #pragma unroll
@@ -118,26 +133,39 @@ __device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint3
   constexpr int B = zc::Traits<RATE>::kBlockBytes;
   uint8_t* p = out + j * B;
   if constexpr (B == 16) {
-    *reinterpret_cast<uint4*>(p) = make_uint4(W[0], W[1], W[2], W[3]);
+    u32x4 v = {W[0], W[1], W[2], W[3]};
+    nt_store(reinterpret_cast<u32x4*>(p), v);
   } else if constexpr (B == 8) {
-    *reinterpret_cast<uint2*>(p) = make_uint2(W[0], W[1]);
+    u32x2 v = {W[0], W[1]};
+    nt_store(reinterpret_cast<u32x2*>(p), v);
   } else if constexpr (B % 4 == 0) {
 #pragma unroll
-    for (int i = 0; i < B / 4; ++i) reinterpret_cast<uint32_t*>(p)[i] = W[i];
+    for (int i = 0; i < B / 4; ++i) nt_store(reinterpret_cast<uint32_t*>(p) + i, W[i]);
   } else {
     uint16_t* h = reinterpret_cast<uint16_t*>(p);
 #pragma unroll
-    for (int i = 0; i < B / 2; ++i) h[i] = (uint16_t)(W[i / 2] >> (16 * (i % 2)));
+    for (int i = 0; i < B / 2; ++i) nt_store(h + i, (uint16_t)(W[i / 2] >> (16 * (i % 2))));
   }
 }
 
 // ---- kernels ------------------------------------------------------------------------
-// Each kernel runs its lanes over the whole blocks with a grid stride, fetching the
-// next block (always an in-bounds address, so the loop body has no branch around the
-// load) before coding the current one; the ragged last block, if any, is left to one
-// lane at the end.
+// Work is cut into tiles of U * 256 consecutive blocks; a workgroup takes tiles with a
+// grid stride and lane t codes blocks t, t + 256, ... of the tile, so every access of
+// a wavefront is one contiguous span.  All U loads of the next tile are issued before
+// the current tile is coded (always from an in-bounds address, so no branch surrounds
+// them): that keeps U accesses per lane in flight, which is what the narrow stream
+// accesses (RATE/2 bytes per lane) need to cover memory latency.  Blocks after the
+// last whole tile are coded one per lane, and the ragged last block (n % 4 values) by
+// a single lane.
 
-template <int RATE>
+// Blocks per lane and tile, from measurements on MI355X: the rate-4 compress and
+// decompress kernels have so little work per block that one block per lane is fastest;
+// everything else gains from four accesses in flight per lane.
+template <int RATE> constexpr int compress_unroll() { return RATE == 4 ? 1 : 4; }
+template <int RATE> constexpr int decompress_unroll() { return RATE == 4 ? 1 : 4; }
+template <int RATE> constexpr int reduce_unroll() { return 4; }
+
+template <int RATE, int U>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restrict__ in, size_t n,
                                                             uint8_t* __restrict__ out) {
   __shared__ __align__(16) uint32_t enc[kEncWords];
@@ -145,25 +173,41 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
   __syncthreads();
   const zc::Tables tab = {enc, nullptr, nullptr};
   constexpr int NW = zc::Traits<RATE>::kWords;
+  constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j < whole) {
-    uint32_t x[4];
-    load_values(in, j, x);
+  const size_t tiles = whole / kTile;
+  size_t t = blockIdx.x;
+  if (t < tiles) {
+    uint32_t x[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_values(in, t * kTile + u * kThreads + threadIdx.x, x[u]);
     while (true) {
-      const size_t jn = j + stride;
-      const bool more = jn < whole;
-      uint32_t xn[4];
-      load_values(in, more ? jn : j, xn);
-      uint32_t W[NW];
-      zc::encode_block<RATE>(x, tab, W, AnyLane());
-      store_stream<RATE>(out, j, W);
+      const size_t tn = t + gridDim.x;
+      const bool more = tn < tiles;
+      const size_t next = (more ? tn : t) * kTile + threadIdx.x;
+      uint32_t xn[U][4];
+#pragma unroll
+      for (int u = 0; u < U; ++u) load_values(in, next + u * kThreads, xn[u]);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        uint32_t W[NW];
+        zc::encode_block<RATE>(x[u], tab, W, AnyLane());
+        store_stream<RATE>(out, t * kTile + u * kThreads + threadIdx.x, W);
+      }
       if (!more) break;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) x[i] = xn[i];
-      j = jn;
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[u][i] = xn[u][i];
+      t = tn;
     }
+  }
+  for (size_t j = tiles * kTile + (size_t)blockIdx.x * kThreads + threadIdx.x; j < whole;
+       j += (size_t)gridDim.x * kThreads) {
+    uint32_t x[4], W[NW];
+    load_values(in, j, x);
+    zc::encode_block<RATE>(x, tab, W, AnyLane());
+    store_stream<RATE>(out, j, W);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t x[4], W[NW];
@@ -173,32 +217,49 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
   }
 }
 
-template <int RATE>
+template <int RATE, int U>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __restrict__ in, size_t n,
                                                               float* __restrict__ out) {
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
   const zc::Tables tab = stage_decoder_table<RATE>(dec, nullptr);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;
+  constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j < whole) {
-    uint32_t W[NW];
-    load_stream<RATE>(in, j, W);
+  const size_t tiles = whole / kTile;
+  size_t t = blockIdx.x;
+  if (t < tiles) {
+    uint32_t W[U][NW];
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_stream<RATE>(in, t * kTile + u * kThreads + threadIdx.x, W[u]);
     while (true) {
-      const size_t jn = j + stride;
-      const bool more = jn < whole;
-      uint32_t Wn[NW];
-      load_stream<RATE>(in, more ? jn : j, Wn);
-      float y[4];
-      zc::decode_block<RATE>(W, tab, y, AnyLane());
-      store_values(out, j, y);
+      const size_t tn = t + gridDim.x;
+      const bool more = tn < tiles;
+      const size_t next = (more ? tn : t) * kTile + threadIdx.x;
+      uint32_t Wn[U][NW];
+#pragma unroll
+      for (int u = 0; u < U; ++u) load_stream<RATE>(in, next + u * kThreads, Wn[u]);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float y[4];
+        zc::decode_block<RATE>(W[u], tab, y, AnyLane());
+        store_values(out, t * kTile + u * kThreads + threadIdx.x, y);
+      }
       if (!more) break;
 #pragma unroll
-      for (int i = 0; i < NW; ++i) W[i] = Wn[i];
-      j = jn;
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
+      t = tn;
     }
+  }
+  for (size_t j = tiles * kTile + (size_t)blockIdx.x * kThreads + threadIdx.x; j < whole;
+       j += (size_t)gridDim.x * kThreads) {
+    uint32_t W[NW];
+    float y[4];
+    load_stream<RATE>(in, j, W);
+    zc::decode_block<RATE>(W, tab, y, AnyLane());
+    store_values(out, j, y);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t W[NW];
@@ -214,11 +275,11 @@ struct ChunkPointers {
 };
 
 // Decode block j of every chunk, add in fp32 in chunk order, encode the sum.  The
-// output may be one of the inputs: a lane reads its block of all chunks before it
-// writes, and no other lane touches that block.  The blocks are visited in the order
-// (j, chunk 0), (j, chunk 1), ..., (j + stride, chunk 0), ... and the next one in that
-// order is fetched before the current one is decoded.
-template <int RATE>
+// output may be one of the inputs: a lane reads its blocks of all chunks before it
+// writes them, and no other lane touches those blocks.  Tiles are visited chunk by
+// chunk, (tile, chunk 0), (tile, chunk 1), ..., (next tile, chunk 0), and the next
+// one in that order is fetched before the current one is decoded.
+template <int RATE, int U>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, size_t n, uint8_t* out) {
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
   __shared__ __align__(16) uint32_t enc[kEncWords];
@@ -226,35 +287,63 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
   const zc::Tables tab = stage_decoder_table<RATE>(dec, enc);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;
+  constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  size_t j = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j < whole) {
-    uint32_t W[NW];
-    load_stream<RATE>(chunks.p[0], j, W);
+  const size_t tiles = whole / kTile;
+  size_t t = blockIdx.x;
+  if (t < tiles) {
+    uint32_t W[U][NW];
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_stream<RATE>(chunks.p[0], t * kTile + u * kThreads + threadIdx.x, W[u]);
     while (true) {
-      const size_t jn = j + stride;
-      const bool more = jn < whole;
-      float s[4];
+      const size_t tn = t + gridDim.x;
+      const bool more = tn < tiles;
+      float s[U][4];
       for (int c = 0; c < k; ++c) {
         const bool last = c + 1 == k;
-        uint32_t Wn[NW];
-        load_stream<RATE>(chunks.p[last ? 0 : c + 1], last ? (more ? jn : j) : j, Wn);
-        float y[4];
-        zc::decode_block<RATE>(W, tab, y, AnyLane());
+        const uint8_t* src = chunks.p[last ? 0 : c + 1];
+        const size_t next = (last ? (more ? tn : t) : t) * kTile + threadIdx.x;
+        uint32_t Wn[U][NW];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
+        for (int u = 0; u < U; ++u) load_stream<RATE>(src, next + u * kThreads, Wn[u]);
 #pragma unroll
-        for (int i = 0; i < NW; ++i) W[i] = Wn[i];
+        for (int u = 0; u < U; ++u) {
+          float y[4];
+          zc::decode_block<RATE>(W[u], tab, y, AnyLane());
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[u][i] = c ? s[u][i] + y[i] : y[i];
+#pragma unroll
+          for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
+        }
       }
-      uint32_t x[4], Wo[NW];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[i]);
-      zc::encode_block<RATE>(x, tab, Wo, AnyLane());
-      store_stream<RATE>(out, j, Wo);
+      for (int u = 0; u < U; ++u) {
+        uint32_t x[4], Wo[NW];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[u][i]);
+        zc::encode_block<RATE>(x, tab, Wo, AnyLane());
+        store_stream<RATE>(out, t * kTile + u * kThreads + threadIdx.x, Wo);
+      }
       if (!more) break;
-      j = jn;
+      t = tn;
     }
+  }
+  for (size_t j = tiles * kTile + (size_t)blockIdx.x * kThreads + threadIdx.x; j < whole;
+       j += (size_t)gridDim.x * kThreads) {
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < k; ++c) {
+      uint32_t W[NW];
+      float y[4];
+      load_stream<RATE>(chunks.p[c], j, W);
+      zc::decode_block<RATE>(W, tab, y, AnyLane());
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
+    }
+    uint32_t x[4], Wo[NW];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[i]);
+    zc::encode_block<RATE>(x, tab, Wo, AnyLane());
+    store_stream<RATE>(out, j, Wo);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     float s[4] = {0.f, 0.f, 0.f, 0.f};
@@ -279,22 +368,47 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 
 // ---- host side ----------------------------------------------------------------------
 
-int grid_cap() {
+int compute_units() {
   static int cached[64] = {0};
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256 * kWorkgroupsPerCU;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
   if (cached[dev] == 0) {
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    cached[dev] = cus * kWorkgroupsPerCU;
+    cached[dev] = cus;
   }
   return cached[dev];
 }
 
-unsigned grid_for(size_t n) {
+// Workgroups per CU in the grid (each loops over tiles with a grid stride).  Eight
+// 256-thread workgroups fill a CU; launching several times that lets the dispatcher
+// even out the data-dependent coding time, which pays for every coder-bound kernel
+// (measured: 32 to 48 per CU is best at rates 8 and up and for the fused reduce),
+// while the rate-4 decompress kernel, bound by its 16-byte stores, is fastest with
+// exactly one resident set.  ZC_WORKGROUPS_PER_CU overrides this for tuning runs.
+enum Kernel { kCompress, kDecompress, kReduce };
+
+int workgroups_per_cu(Kernel kernel, int rate) {
+  static int forced = -1;
+  if (forced < 0) {
+    forced = 0;
+    if (const char* e = getenv("ZC_WORKGROUPS_PER_CU")) {
+      int v = atoi(e);
+      if (v >= 1 && v <= 64) forced = v;
+    }
+  }
+  if (forced > 0) return forced;
+  switch (kernel) {
+    case kCompress: return rate == 4 ? 16 : 32;
+    case kDecompress: return rate == 4 ? 8 : 32;
+    default: return 48;
+  }
+}
+
+unsigned grid_for(size_t n, Kernel kernel, int rate) {
   size_t blocks = (n + 3) / 4;
   size_t groups = (blocks + kThreads - 1) / kThreads;
-  size_t cap = (size_t)grid_cap();
+  size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu(kernel, rate);
   return (unsigned)(groups < cap ? groups : cap);
 }
 
@@ -363,7 +477,7 @@ int zc_compress(const float* d_in, size_t n, int rate, void* d_out, size_t out_c
   if (n > kMaxValues) return ZC_ERR_SIZE;
   if (out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL(compress_kernel<R>, dim3(grid_for(n)), dim3(kThreads), 0, s, d_in, n, static_cast<uint8_t*>(d_out))
+#define CALL(R) hipLaunchKernelGGL((compress_kernel<R, compress_unroll<R>()>), dim3(grid_for(n, kCompress, R)), dim3(kThreads), 0, s, d_in, n, static_cast<uint8_t*>(d_out))
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return finish_launch();
@@ -376,7 +490,7 @@ int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stre
   if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
   if (n > kMaxValues) return ZC_ERR_SIZE;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL(decompress_kernel<R>, dim3(grid_for(n)), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), n, d_out)
+#define CALL(R) hipLaunchKernelGGL((decompress_kernel<R, decompress_unroll<R>()>), dim3(grid_for(n, kDecompress, R)), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), n, d_out)
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return finish_launch();
@@ -399,7 +513,7 @@ int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, voi
   if (n > kMaxValues) return ZC_ERR_SIZE;
   if (out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL(reduce_kernel<R>, dim3(grid_for(n)), dim3(kThreads), 0, s, chunks, k, n, static_cast<uint8_t*>(d_out))
+#define CALL(R) hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>()>), dim3(grid_for(n, kReduce, R)), dim3(kThreads), 0, s, chunks, k, n, static_cast<uint8_t*>(d_out))
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return finish_launch();

@@ -8,8 +8,8 @@
 namespace {
 const zc::EncTable kEnc = zc::build_enc_table();
 const zc::DecTable kDec = zc::build_dec_table();
-const zc::Dec8Table kDec8 = zc::build_dec8_table();
-const zc::Tables kTables = {kEnc.v, kDec.v, kDec8.v};
+const zc::Dec4Table kDec4 = zc::build_dec4_table();
+const zc::Tables kTables = {kEnc.v, kDec.v, kDec4.v};
 auto always = [](bool p) { return p; };
 
 template <int RATE>
