@@ -24,10 +24,12 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
 INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one int32 op per lane-clock
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# workload (profiles/), scaled by the same counters on a copy of known size.
-# None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# From the rocprofv3 --pmc runs of this same workload summarised under profiles/:
+# HBM bytes per launch (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, the scale a 1 GiB
+# device copy gives on this machine) and wave-level VALU instructions per launch
+# (SQ_INSTS_VALU; x 64 lanes = lane operations).
+MEASURED_TRAFFIC_BYTES = {"compress": 1216572383, "decompress": 1208026998, "reduce": 402845009}
+MEASURED_VALU_WAVE_INSTS = {"compress": 85413592, "decompress": 13762560, "reduce": 109247182}
 
 
 def algorithmic_bytes(kernel, n, rate, k=2):
@@ -158,11 +160,19 @@ def main():
     avg_ms = {nm: float(np.mean([m[i].elapsed_time(m[i + 1]) for m in marks])) for i, nm in enumerate(names)}
     dominant = max(avg_ms, key=avg_ms.get)
     abytes = algorithmic_bytes(dominant, n, rate, k=2)
-    achieved = abytes / (avg_ms[dominant] * 1e-3) / 1e9
-    roofline = {"kernel": dominant + "_kernel<%d>" % rate, "bound": "hbm", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_launch_ms": round(avg_ms[dominant], 4),
-                "algorithmic_bytes": abytes}
+    if dominant == "reduce":
+        # two decodes and one encode per 6 bytes of traffic: bound by integer VALU work
+        ops = MEASURED_VALU_WAVE_INSTS[dominant] * 64
+        achieved = ops / (avg_ms[dominant] * 1e-3) / 1e12
+        roofline = {"kernel": dominant + "_kernel<%d>" % rate, "bound": "alu", "achieved": round(achieved, 2),
+                    "peak": round(INT_ALU_PEAK_TOPS, 2), "unit": "Tops/s (int32 lane operations)",
+                    "frac": round(achieved / INT_ALU_PEAK_TOPS, 4), "lane_ops_per_launch": ops}
+    else:
+        achieved = abytes / (avg_ms[dominant] * 1e-3) / 1e9
+        roofline = {"kernel": dominant + "_kernel<%d>" % rate, "bound": "hbm", "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
+    roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_launch_ms": round(avg_ms[dominant], 4),
+                     "algorithmic_bytes": abytes})
     kernels = {nm: {"avg_ms": round(avg_ms[nm], 4),
                     "uncompressed_GBps": round(4 * n / (avg_ms[nm] * 1e-3) / 1e9, 1),
                     "algorithmic_GBps": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9, 1),
