@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time every kernel on all five configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the 1 GiB input (known traffic, for scaling profiler counters)")
+    ap.add_argument("--rates", type=int, nargs="+", default=None,
+                    help="instead of the benchmark line: time the same three-call step at these rates on 2^28 values "
+                         "(gradient bucket below rate 16, GELU activations from rate 16 up); one JSON list on stdout")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -112,6 +115,10 @@ def main():
     zc.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.rates:
+        print(json.dumps(rate_loop(torch, zc, workloads, dev, args.rates)))
+        return
 
     cfg = workloads.CONFIGS[2]
     rate, n = cfg["rate"], cfg["n"]
@@ -210,6 +217,42 @@ def main():
         threads = min(16, len(os.sched_getaffinity(0)))
         result["cpu_baseline"] = cpu_baseline(x_host, rate, 1 << args.cpu_sample_log2, threads)
     print(json.dumps(result))
+
+
+def rate_loop(torch, zc, workloads, dev, rates, reps=12):
+    """compress -> 2-way reduce -> decompress on 2^28 values at each rate, per-kernel
+    medians from HIP events on the launch stream."""
+    n = 1 << 28
+    grad = torch.from_numpy(workloads.config_buffers(2)[0][1]).to(dev)
+    act = torch.from_numpy(workloads.activation_gelu(n)).to(dev) if any(r >= 16 for r in rates) else None
+    y = torch.empty(n, dtype=torch.float32, device=dev)
+    out = []
+    for rate in rates:
+        x = grad if rate < 16 else act
+        c = zc.zc_compress(x, rate)
+        peer = zc.zc_compress(torch.flip(x, [0]).contiguous(), rate)
+        r = torch.empty_like(c)
+        marks = []
+        for _ in range(reps):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            e[0].record()
+            zc.zc_compress(x, rate, d_out=c)
+            e[1].record()
+            zc.zc_reduce_compressed([peer, c], n, rate, d_out=r)
+            e[2].record()
+            zc.zc_decompress(r, n, rate, d_out=y)
+            e[3].record()
+            marks.append(e)
+        torch.cuda.synchronize()
+        ms = [float(np.median([m[i].elapsed_time(m[i + 1]) for m in marks[2:]])) for i in range(3)]
+        ab = algorithmic_bytes("compress", n, rate)
+        out.append({"rate": rate, "data": "gradient bucket" if rate < 16 else "gelu activations",
+                    "compress_ms": round(ms[0], 4), "reduce_k2_ms": round(ms[1], 4), "decompress_ms": round(ms[2], 4),
+                    "compress_hbm_frac": round(ab / (ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "decompress_hbm_frac": round(ab / (ms[2] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "reduce_uncompressed_GBps": round(4 * n / (ms[1] * 1e-3) / 1e9, 1)})
+        del c, peer, r
+    return out
 
 
 def sweep(torch, zc, workloads, dev):
