@@ -314,3 +314,79 @@ int zc_ref_reduce_compressed(const void *const *in, int k, size_t n, int rate,
   }
   return ZC_REF_OK;
 }
+
+/* ---- ring-hop variants of the reduce step -------------------------------- */
+
+/* Sum of block j over the k chunks and, if `local` is given, the raw local
+ * values added last: ((d0 + d1) + ... + d_{k-1}) + x.  Lanes beyond n take
+ * the local pad rule (last valid value repeated) before the add; they are
+ * replaced by the caller anyway. */
+static void sum_block(const void *const *in, int k, const float *local, size_t n, size_t j,
+                      int rate, float s[4]) {
+  size_t bit0 = j * (size_t)(4 * rate);
+  float d[4];
+  if (k > 0) {
+    decode_block((const uint8_t *)in[0], bit0, rate, s);
+  } else {
+    s[0] = s[1] = s[2] = s[3] = 0.0f;
+  }
+  for (int c = 1; c < k; ++c) {
+    decode_block((const uint8_t *)in[c], bit0, rate, d);
+    for (int i = 0; i < 4; ++i) {
+      volatile float t = s[i] + d[i];
+      s[i] = t;
+    }
+  }
+  if (local) {
+    load_block(local, n, j, d);
+    for (int i = 0; i < 4; ++i) {
+      volatile float t = s[i] + d[i];
+      s[i] = t;
+    }
+  }
+}
+
+/* A ring hop whose local contribution is still raw fp32 (Sec. IV-A: each
+ * rank adds its own gradients to what it received before forwarding):
+ * out = compress(((d0 + ... + d_{k-1}) + local)).  k >= 1; local may be NULL,
+ * which makes this zc_ref_reduce_compressed. */
+int zc_ref_reduce_mixed(const void *const *in, int k, const float *local, size_t n, int rate,
+                        void *out, size_t out_cap) {
+  if (!zc_ref_rate_supported(rate)) return ZC_REF_ERR_RATE;
+  if (k < 1 || k > 16) return ZC_REF_ERR_K;
+  if (n == 0) return ZC_REF_OK;
+  if (!in || !out) return ZC_REF_ERR_NULL;
+  for (int c = 0; c < k; ++c)
+    if (!in[c]) return ZC_REF_ERR_NULL;
+  if (out_cap < zc_ref_compressed_size(n, rate)) return ZC_REF_ERR_CAPACITY;
+  size_t blocks = (n + 3) / 4;
+  for (size_t j = 0; j < blocks; ++j) {
+    float s[4];
+    sum_block(in, k, local, n, j, rate, s);
+    for (int i = 0; i < 4; ++i)
+      if (4 * j + (size_t)i >= n) s[i] = s[(n - 1) - 4 * j];
+    encode_block(s, rate, (uint8_t *)out, j * (size_t)(4 * rate));
+  }
+  return ZC_REF_OK;
+}
+
+/* The last hop, where the sum is wanted as fp32: out[i] = ((d0 + ... +
+ * d_{k-1}) + local)[i], nothing re-encoded.  local may be NULL. */
+int zc_ref_reduce_decompress(const void *const *in, int k, const float *local, size_t n, int rate,
+                             float *out) {
+  if (!zc_ref_rate_supported(rate)) return ZC_REF_ERR_RATE;
+  if (k < 1 || k > 16) return ZC_REF_ERR_K;
+  if (n == 0) return ZC_REF_OK;
+  if (!in || !out) return ZC_REF_ERR_NULL;
+  for (int c = 0; c < k; ++c)
+    if (!in[c]) return ZC_REF_ERR_NULL;
+  size_t blocks = (n + 3) / 4;
+  for (size_t j = 0; j < blocks; ++j) {
+    float s[4];
+    sum_block(in, k, local, n, j, rate, s);
+    for (int i = 0; i < 4; ++i)
+      if (4 * j + (size_t)i < n) out[4 * j + (size_t)i] = s[i];
+  }
+  return ZC_REF_OK;
+}
+

@@ -54,6 +54,10 @@ def lib():
         L.zc_ref_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
                                                ctypes.c_size_t, ctypes.c_int,
                                                ctypes.c_void_p, ctypes.c_size_t]
+        L.zc_ref_reduce_mixed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+        L.zc_ref_reduce_decompress.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -171,4 +175,41 @@ def reduce_compressed(streams, n, rate):
     rc = lib().zc_ref_reduce_compressed(ptrs, k, int(n), int(rate), out.ctypes.data, out.size)
     if rc != 0:
         raise ValueError("zc_ref_reduce_compressed failed: %d" % rc)
+    return out
+
+
+def _chunk_pointers(streams, n, rate):
+    ss = [np.ascontiguousarray(s, dtype=np.uint8) for s in streams]
+    size = compressed_size(n, rate)
+    for s in ss:
+        if s.size < size:
+            raise ValueError("stream too short")
+    return ss, (ctypes.c_void_p * max(len(ss), 1))(*[s.ctypes.data for s in ss])
+
+
+def reduce_mixed(streams, local, n, rate):
+    """compress((d_0 + ... + d_{k-1}) + local); local is a raw fp32 array or None."""
+    ss, ptrs = _chunk_pointers(streams, n, rate)
+    loc = None if local is None else _f32(local).reshape(-1)
+    if loc is not None and loc.size < n:
+        raise ValueError("local too short")
+    out = np.zeros(compressed_size(n, rate), dtype=np.uint8)
+    rc = lib().zc_ref_reduce_mixed(ptrs, len(ss), None if loc is None else loc.ctypes.data, int(n), int(rate),
+                                   out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError("zc_ref_reduce_mixed failed: %d" % rc)
+    return out
+
+
+def reduce_decompress(streams, local, n, rate):
+    """(d_0 + ... + d_{k-1}) + local as fp32; local is a raw fp32 array or None."""
+    ss, ptrs = _chunk_pointers(streams, n, rate)
+    loc = None if local is None else _f32(local).reshape(-1)
+    if loc is not None and loc.size < n:
+        raise ValueError("local too short")
+    out = np.zeros(n, dtype=np.float32)
+    rc = lib().zc_ref_reduce_decompress(ptrs, len(ss), None if loc is None else loc.ctypes.data, int(n), int(rate),
+                                        out.ctypes.data)
+    if rc != 0:
+        raise ValueError("zc_ref_reduce_decompress failed: %d" % rc)
     return out

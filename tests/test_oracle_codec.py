@@ -240,3 +240,37 @@ def test_reduce_argument_checks(oracle):
         oracle.reduce_compressed([c] * 17, 8, 8)
     assert np.array_equal(oracle.reduce_compressed([c] * 16, 8, 8),
                           oracle.compress(np.full(8, 16, dtype=np.float32), 8))
+
+
+def test_ring_hop_variants_are_compositions(oracle):
+    """reduce_mixed == compress((sum of decoded chunks) + local) and reduce_decompress ==
+    that sum itself, with every add done by numpy in fp32 in the stated order."""
+    n = 4096 + 3
+    peers = [workloads.gradient_lowrank(64, 64, tail=3, config=5, index=p) for p in range(5)]
+    local = workloads.gradient_lowrank(64, 64, tail=3, config=5, index=7)
+    for rate in (4, 8, 16, 24):
+        comp = [oracle.compress(p, rate) for p in peers]
+        dec = [oracle.decompress(c, n, rate) for c in comp]
+        for k in (1, 2, 5):
+            s = dec[0].copy()
+            for j in range(1, k):
+                s = (s + dec[j]).astype(np.float32)
+            assert np.array_equal(oracle.reduce_decompress(comp[:k], None, n, rate).view(np.uint32), s.view(np.uint32))
+            assert np.array_equal(oracle.reduce_mixed(comp[:k], None, n, rate), oracle.reduce_compressed(comp[:k], n, rate))
+            t = (s + local).astype(np.float32)
+            assert np.array_equal(oracle.reduce_decompress(comp[:k], local, n, rate).view(np.uint32), t.view(np.uint32))
+            assert np.array_equal(oracle.reduce_mixed(comp[:k], local, n, rate), oracle.compress(t, rate))
+    # a full ring on one rank's share: first hop has only raw data on both sides
+    rate, acc = 8, None
+    raw = [workloads.gradient_lowrank(64, 64, tail=3, config=5, index=p) for p in range(4)]
+    acc = oracle.compress(raw[0], rate)
+    ref = raw[0]
+    for p in (1, 2):
+        acc = oracle.reduce_mixed([acc], raw[p], n, rate)
+        ref = (oracle.decompress(oracle.compress(ref, rate), n, rate) + raw[p]).astype(np.float32)
+    final = oracle.reduce_decompress([acc], raw[3], n, rate)
+    want = (oracle.decompress(oracle.compress(ref, rate), n, rate) + raw[3]).astype(np.float32)
+    assert np.array_equal(final.view(np.uint32), want.view(np.uint32))
+    with pytest.raises(ValueError):
+        oracle.reduce_mixed([], local, n, 8)
+
