@@ -96,6 +96,24 @@ int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stre
 int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, void* d_out,
                          size_t out_cap, void* stream);
 
+/* A ring hop of the compressed reduce-scatter in which this rank's own contribution
+ * is still raw fp32 (Sec. IV-A: every rank adds its gradients to the chunk it received
+ * and forwards the result): writes the compressed form of
+ * ((x_0 + ... + x_{k-1}) + local), x_j = decompressed chunk j, every add in fp32.
+ * d_in as in zc_reduce_compressed (k in [1, 16]); d_local holds n fp32 values and may
+ * be NULL, which makes this call zc_reduce_compressed.  d_out may be one of the inputs
+ * d_in[j] but must not overlap d_local. */
+int zc_reduce_mixed(const void* const* d_in, int k, const float* d_local, size_t n, int rate,
+                    void* d_out, size_t out_cap, void* stream);
+
+/* The last hop, where the sum is consumed uncompressed: d_out[i] =
+ * ((x_0 + ... + x_{k-1}) + local)[i] as fp32, nothing re-encoded.  d_local may be NULL;
+ * with k = 1 and d_local = NULL this is zc_decompress.  d_out (n values) may be the same
+ * buffer as d_local (each value is read before it is written) but must not overlap
+ * any d_in[j]. */
+int zc_reduce_decompress(const void* const* d_in, int k, const float* d_local, size_t n, int rate,
+                         float* d_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -274,22 +274,44 @@ struct ChunkPointers {
   const uint8_t* p[kMaxChunks];
 };
 
-// Decode block j of every chunk, add in fp32 in chunk order, encode the sum.  The
-// output may be one of the inputs: a lane reads its blocks of all chunks before it
-// writes them, and no other lane touches those blocks.  Tiles are visited chunk by
-// chunk, (tile, chunk 0), (tile, chunk 1), ..., (next tile, chunk 0), and the next
-// one in that order is fetched before the current one is decoded.
-template <int RATE, int U>
-__global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, size_t n, uint8_t* out) {
+// The fused reduce.  Decode block j of every chunk, add in fp32 in chunk order, add
+// the raw local values last if there are any (LOCAL), then either encode the sum or
+// store it as fp32 (RAW_OUT).  Nothing but the inputs and the output touches memory.
+// The output may be one of the inputs of the same kind: a lane reads its blocks of all
+// inputs before it writes them, and no other lane touches those blocks.  Tiles are
+// visited chunk by chunk, (tile, chunk 0), (tile, chunk 1), ..., (next tile, chunk 0),
+// and the next one in that order is fetched before the current one is decoded; the
+// local values of a tile are requested before its first chunk is decoded.
+template <int RATE, int U, bool LOCAL, bool RAW_OUT>
+__global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, const float* local, size_t n,
+                                                          uint8_t* out, float* out_raw) {
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
-  __shared__ __align__(16) uint32_t enc[kEncWords];
-  stage_table<kEncWords>(enc, g_enc_table.v);
+  __shared__ __align__(16) uint32_t enc[RAW_OUT ? 4 : kEncWords];
+  if constexpr (!RAW_OUT) stage_table<kEncWords>(enc, g_enc_table.v);
   const zc::Tables tab = stage_decoder_table<RATE>(dec, enc);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;
   constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
   const size_t tiles = whole / kTile;
+
+  // s: the sum of one block; finishes it (local add, then encode or store)
+  auto finish = [&](float (&s)[4], const uint32_t (&loc)[4], size_t j) {
+    if constexpr (LOCAL) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s[i] += __uint_as_float(loc[i]);
+    }
+    if constexpr (RAW_OUT) {
+      store_values(out_raw, j, s);
+    } else {
+      uint32_t x[4], Wo[NW];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[i]);
+      zc::encode_block<RATE>(x, tab, Wo, AnyLane());
+      store_stream<RATE>(out, j, Wo);
+    }
+  };
+
   size_t t = blockIdx.x;
   if (t < tiles) {
     uint32_t W[U][NW];
@@ -298,6 +320,11 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
     while (true) {
       const size_t tn = t + gridDim.x;
       const bool more = tn < tiles;
+      uint32_t loc[U][4];
+      if constexpr (LOCAL) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) load_values(local, t * kTile + u * kThreads + threadIdx.x, loc[u]);
+      }
       float s[U][4];
       for (int c = 0; c < k; ++c) {
         const bool last = c + 1 == k;
@@ -317,20 +344,14 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
         }
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        uint32_t x[4], Wo[NW];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[u][i]);
-        zc::encode_block<RATE>(x, tab, Wo, AnyLane());
-        store_stream<RATE>(out, t * kTile + u * kThreads + threadIdx.x, Wo);
-      }
+      for (int u = 0; u < U; ++u) finish(s[u], loc[u], t * kTile + u * kThreads + threadIdx.x);
       if (!more) break;
       t = tn;
     }
   }
-  for (size_t j = tiles * kTile + (size_t)blockIdx.x * kThreads + threadIdx.x; j < whole;
-       j += (size_t)gridDim.x * kThreads) {
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
+
+  // sum of one block read directly (blocks after the last whole tile, and the ragged block)
+  auto direct_sum = [&](size_t j, float (&s)[4]) {
     for (int c = 0; c < k; ++c) {
       uint32_t W[NW];
       float y[4];
@@ -339,30 +360,36 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 #pragma unroll
       for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
     }
-    uint32_t x[4], Wo[NW];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(s[i]);
-    zc::encode_block<RATE>(x, tab, Wo, AnyLane());
-    store_stream<RATE>(out, j, Wo);
+  };
+  for (size_t j = tiles * kTile + (size_t)blockIdx.x * kThreads + threadIdx.x; j < whole;
+       j += (size_t)gridDim.x * kThreads) {
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    uint32_t loc[4] = {0, 0, 0, 0};
+    if constexpr (LOCAL) load_values(local, j, loc);
+    direct_sum(j, s);
+    finish(s, loc, j);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     float s[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < k; ++c) {
-      uint32_t W[NW];
-      float y[4];
-      load_stream<RATE>(chunks.p[c], whole, W);
-      zc::decode_block<RATE>(W, tab, y, AnyLane());
+    direct_sum(whole, s);
+    if constexpr (LOCAL) {
+      uint32_t loc[4];
+      load_values_ragged(local, n, loc);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s[i] = c ? s[i] + y[i] : y[i];
+      for (int i = 0; i < 4; ++i) s[i] += __uint_as_float(loc[i]);
     }
-    // the result is compress(sum): the pad repeats the last valid sum
-    const int valid = (int)(n & 3);
-    const float pad = valid == 1 ? s[0] : (valid == 2 ? s[1] : s[2]);
-    uint32_t x[4], Wo[NW];
+    if constexpr (RAW_OUT) {
+      store_values_ragged(out_raw, n, s);
+    } else {
+      // the result is compress(sum): the pad repeats the last valid sum
+      const int valid = (int)(n & 3);
+      const float pad = valid == 1 ? s[0] : (valid == 2 ? s[1] : s[2]);
+      uint32_t x[4], Wo[NW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(i < valid ? s[i] : pad);
-    zc::encode_block<RATE>(x, tab, Wo, AnyLane());
-    store_stream<RATE>(out, whole, Wo);
+      for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(i < valid ? s[i] : pad);
+      zc::encode_block<RATE>(x, tab, Wo, AnyLane());
+      store_stream<RATE>(out, whole, Wo);
+    }
   }
 }
 
@@ -496,12 +523,13 @@ int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stre
   return finish_launch();
 }
 
-int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, void* d_out, size_t out_cap,
-                         void* stream) {
+static int launch_reduce(const void* const* d_in, int k, const float* d_local, size_t n, int rate, void* d_out,
+                         size_t out_cap, float* d_out_raw, void* stream) {
+  const bool raw_out = d_out_raw != nullptr;
   if (!zc_rate_supported(rate)) return ZC_ERR_RATE;
   if (k < 1 || k > kMaxChunks) return ZC_ERR_K;
   if (n == 0) return ZC_OK;
-  if (!d_in || !d_out) return ZC_ERR_NULL;
+  if (!d_in || (!raw_out && !d_out)) return ZC_ERR_NULL;
   ChunkPointers chunks;
   for (int c = 0; c < kMaxChunks; ++c) chunks.p[c] = nullptr;
   for (int c = 0; c < k; ++c) {
@@ -509,14 +537,41 @@ int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, voi
     if (!aligned16(d_in[c])) return ZC_ERR_ALIGN;
     chunks.p[c] = static_cast<const uint8_t*>(d_in[c]);
   }
-  if (!aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (!aligned16(d_out) || !aligned16(d_out_raw) || !aligned16(d_local)) return ZC_ERR_ALIGN;
   if (n > kMaxValues) return ZC_ERR_SIZE;
-  if (out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
+  if (!raw_out && out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>()>), dim3(grid_for(n, kReduce, R)), dim3(kThreads), 0, s, chunks, k, n, static_cast<uint8_t*>(d_out))
+  uint8_t* out = static_cast<uint8_t*>(d_out);
+#define LAUNCH(R, LOCAL, RAW)                                                                                 \
+  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW>), dim3(grid_for(n, kReduce, R)),       \
+                     dim3(kThreads), 0, s, chunks, k, d_local, n, out, d_out_raw)
+#define CALL(R)                                   \
+  do {                                            \
+    if (d_local && raw_out) LAUNCH(R, true, true);        \
+    else if (d_local) LAUNCH(R, true, false);     \
+    else if (raw_out) LAUNCH(R, false, true);     \
+    else LAUNCH(R, false, false);                 \
+  } while (0)
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
+#undef LAUNCH
   return finish_launch();
+}
+
+int zc_reduce_compressed(const void* const* d_in, int k, size_t n, int rate, void* d_out, size_t out_cap,
+                         void* stream) {
+  return launch_reduce(d_in, k, nullptr, n, rate, d_out, out_cap, nullptr, stream);
+}
+
+int zc_reduce_mixed(const void* const* d_in, int k, const float* d_local, size_t n, int rate, void* d_out,
+                    size_t out_cap, void* stream) {
+  return launch_reduce(d_in, k, d_local, n, rate, d_out, out_cap, nullptr, stream);
+}
+
+int zc_reduce_decompress(const void* const* d_in, int k, const float* d_local, size_t n, int rate, float* d_out,
+                         void* stream) {
+  if (zc_rate_supported(rate) && k >= 1 && k <= kMaxChunks && n != 0 && !d_out) return ZC_ERR_NULL;
+  return launch_reduce(d_in, k, d_local, n, rate, nullptr, 0, d_out, stream);
 }
 
 }  // extern "C"

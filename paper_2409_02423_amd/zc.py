@@ -18,7 +18,7 @@ ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH = -5, -6, -7
 ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE = range(5)
 
 EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
-           "zc_compress", "zc_decompress", "zc_reduce_compressed")
+           "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress")
 
 _lib = None
 
@@ -53,6 +53,10 @@ def lib():
                                     ctypes.c_void_p]
         L.zc_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t,
                                            ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.zc_reduce_mixed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                      ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.zc_reduce_decompress.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
+                                           ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -148,3 +152,57 @@ def zc_reduce_compressed(d_in, n, rate, d_out=None, stream=None):
     if rc != ZC_OK:
         raise ZcError(rc, "zc_reduce_compressed")
     return d_out
+
+
+def _chunk_array(d_in, n, rate, what):
+    chunks = list(d_in)
+    need = zc_compressed_size(n, rate)
+    if need == 0 and n != 0:
+        raise ZcError(ZC_ERR_RATE, what)
+    for c in chunks:
+        _check_device_tensor(c, torch.uint8, "every chunk")
+        if c.numel() < need:
+            raise ValueError("a chunk holds %d bytes, need %d" % (c.numel(), need))
+    return chunks, (ctypes.c_void_p * max(len(chunks), 1))(*[c.data_ptr() for c in chunks])
+
+
+def _local_pointer(d_local, n):
+    if d_local is None:
+        return None
+    _check_device_tensor(d_local, torch.float32, "d_local")
+    if d_local.numel() < n:
+        raise ValueError("d_local holds %d values, need %d" % (d_local.numel(), n))
+    return d_local.data_ptr()
+
+
+def zc_reduce_mixed(d_in, d_local, n, rate, d_out=None, stream=None):
+    """k compressed chunks plus raw fp32 local values (or None) -> compressed sum."""
+    chunks, ptrs = _chunk_array(d_in, n, rate, "zc_reduce_mixed")
+    local = _local_pointer(d_local, n)
+    if d_out is None:
+        device = chunks[0].device if chunks else torch.device("cuda")
+        d_out = _new_stream_buffer(n, rate, device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zc_reduce_mixed(ptrs, len(chunks), local, int(n), int(rate), d_out.data_ptr(), d_out.numel(),
+                               _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_reduce_mixed")
+    return d_out
+
+
+def zc_reduce_decompress(d_in, d_local, n, rate, d_out=None, stream=None):
+    """k compressed chunks plus raw fp32 local values (or None) -> fp32 sum."""
+    chunks, ptrs = _chunk_array(d_in, n, rate, "zc_reduce_decompress")
+    local = _local_pointer(d_local, n)
+    if d_out is None:
+        device = chunks[0].device if chunks else torch.device("cuda")
+        d_out = torch.empty(n, dtype=torch.float32, device=device)
+    _check_device_tensor(d_out, torch.float32, "d_out")
+    if d_out.numel() < n:
+        raise ValueError("d_out holds %d values, need %d" % (d_out.numel(), n))
+    rc = lib().zc_reduce_decompress(ptrs, len(chunks), local, int(n), int(rate), d_out.data_ptr(),
+                                    _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_reduce_decompress")
+    return d_out
+

@@ -73,6 +73,16 @@ def test_argument_errors_come_before_any_launch():
     assert L.zc_reduce_compressed((ctypes.c_void_p * 2)(good, None), 2, 16, 8, good, 100, None) == zc.ZC_ERR_NULL
     assert L.zc_reduce_compressed((ctypes.c_void_p * 2)(good, odd), 2, 16, 8, good, 100, None) == zc.ZC_ERR_ALIGN
     assert L.zc_reduce_compressed(two, 2, 0, 8, None, 0, None) == zc.ZC_OK
+    assert L.zc_reduce_mixed(two, 2, good, 16, 8, good, 15, None) == zc.ZC_ERR_CAPACITY
+    assert L.zc_reduce_mixed(two, 2, odd, 16, 8, good, 100, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_reduce_mixed(two, 0, good, 16, 8, good, 100, None) == zc.ZC_ERR_K
+    assert L.zc_reduce_mixed(two, 2, good, 16, 8, None, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc_reduce_mixed(two, 2, None, 0, 8, None, 0, None) == zc.ZC_OK
+    assert L.zc_reduce_decompress(two, 2, good, 16, 8, None, None) == zc.ZC_ERR_NULL
+    assert L.zc_reduce_decompress(two, 2, good, 16, 8, odd, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_reduce_decompress(two, 17, good, 16, 8, good, None) == zc.ZC_ERR_K
+    assert L.zc_reduce_decompress(two, 2, good, 16, 6, good, None) == zc.ZC_ERR_RATE
+    assert L.zc_reduce_decompress(two, 2, None, 0, 8, None, None) == zc.ZC_OK
 
 
 def test_binding_rejects_host_tensors():

@@ -203,6 +203,48 @@ def test_ring_chain_in_place(gpu, oracle):
     _assert_bytes_equal(_host(gpu.zc_reduce_compressed([_dev(c) for c in comp], n, rate)), want8, 2, "k=8")
 
 
+@pytest.mark.parametrize("rate", MAIN_RATES)
+def test_ring_hop_variants_match_reference(gpu, oracle, rate):
+    """Compressed chunks plus raw local values -> compressed sum, and -> fp32 sum."""
+    n = 4 * 5000 + 1   # four whole tiles of 1024 blocks, a partial tile, a ragged block
+    peers = [workloads.gradient_lowrank(70, 285, tail=n - 70 * 285, config=5, index=p) for p in range(4)]
+    local = workloads.gradient_lowrank(70, 285, tail=n - 70 * 285, config=5, index=9)
+    comp = [oracle.compress(p, rate) for p in peers]
+    dcomp = [_dev(c) for c in comp]
+    dlocal = _dev(local)
+    for k in (1, 2, 4):
+        print("ring hop rate", rate, "k", k, flush=True)
+        for loc, dloc in ((local, dlocal), (None, None)):
+            want = oracle.reduce_mixed(comp[:k], loc, n, rate)
+            got = gpu.zc_reduce_mixed(dcomp[:k], dloc, n, rate)
+            _assert_bytes_equal(_host(got), want, rate // 2, "mixed r%d k%d local=%s" % (rate, k, loc is not None))
+            want = oracle.reduce_decompress(comp[:k], loc, n, rate)
+            got = gpu.zc_reduce_decompress(dcomp[:k], dloc, n, rate)
+            _assert_floats_equal(_host(got), want, "to-raw r%d k%d local=%s" % (rate, k, loc is not None))
+    # in place: the accumulator chunk is overwritten, the fp32 sum lands in the local buffer
+    acc = dcomp[0].clone()
+    gpu.zc_reduce_mixed([acc], dlocal, n, rate, d_out=acc)
+    _assert_bytes_equal(_host(acc), oracle.reduce_mixed(comp[:1], local, n, rate), rate // 2, "mixed in place")
+    buf = dlocal.clone()
+    gpu.zc_reduce_decompress(dcomp[:2], buf, n, rate, d_out=buf)
+    _assert_floats_equal(_host(buf), oracle.reduce_decompress(comp[:2], local, n, rate), "to-raw in place")
+
+
+def test_full_ring_on_one_share(gpu, oracle):
+    """What one rank does to its share over a whole compressed ring all-reduce with raw
+    local gradients: compress, six mixed hops, and a final hop to fp32."""
+    rate, n = 8, 1 << 16
+    raw = [workloads.gradient_lowrank(256, 256, config=5, index=p) for p in range(8)]
+    acc_ref = oracle.compress(raw[0], rate)
+    acc = gpu.zc_compress(_dev(raw[0]), rate)
+    for p in range(1, 7):
+        acc_ref = oracle.reduce_mixed([acc_ref], raw[p], n, rate)
+        gpu.zc_reduce_mixed([acc], _dev(raw[p]), n, rate, d_out=acc)
+    _assert_bytes_equal(_host(acc), acc_ref, rate // 2, "ring accumulator")
+    _assert_floats_equal(_host(gpu.zc_reduce_decompress([acc], _dev(raw[7]), n, rate)),
+                         oracle.reduce_decompress([acc_ref], raw[7], n, rate), "ring result")
+
+
 # ---- full-size configurations, sampled comparison -------------------------------------------------
 
 def _sample_ranges(blocks, count, length, seed):
@@ -248,6 +290,9 @@ def test_full_size_ring_share_sampled(gpu, oracle):
         gpu.zc_reduce_compressed([acc, dcomp[j]], n, rate, d_out=acc)
     final = gpu.zc_decompress(acc, n, rate)
     all8 = gpu.zc_reduce_compressed(dcomp, n, rate)
+    dlocal = _dev(peers[7])
+    mixed = gpu.zc_reduce_mixed(dcomp[:2], dlocal, n, rate)
+    to_raw = gpu.zc_reduce_decompress(dcomp[:2], dlocal, n, rate)
     length = 2048
     for b0 in _sample_ranges(n // 4, 24, length, seed=5):
         print("ring share blocks from", b0, flush=True)
@@ -262,3 +307,7 @@ def test_full_size_ring_share_sampled(gpu, oracle):
         _assert_floats_equal(_host(final[sl]), oracle.decompress(ref, 4 * length, rate), "final from %d" % b0)
         _assert_bytes_equal(_host(all8[b0 * bb:(b0 + length) * bb]),
                             oracle.reduce_compressed(comp, 4 * length, rate), bb, "k=8 from %d" % b0)
+        _assert_bytes_equal(_host(mixed[b0 * bb:(b0 + length) * bb]),
+                            oracle.reduce_mixed(comp[:2], peers[7][sl], 4 * length, rate), bb, "mixed from %d" % b0)
+        _assert_floats_equal(_host(to_raw[sl]), oracle.reduce_decompress(comp[:2], peers[7][sl], 4 * length, rate),
+                             "to-raw from %d" % b0)
