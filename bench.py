@@ -186,6 +186,15 @@ def main():
                     "hbm_frac": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
                for nm in names}
 
+    # the two fused ring-hop variants on the same buffers (not part of `value`)
+    hop_mixed = float(np.median(time_events(lambda: zc.zc_reduce_mixed([incoming], x, n, rate, d_out=r), 12, torch)[2:]))
+    hop_raw = float(np.median(time_events(lambda: zc.zc_reduce_decompress([incoming], x, n, rate, d_out=y), 12, torch)[2:]))
+    mixed_bytes = n * 4 + 2 * (n * rate // 8)
+    raw_bytes = 2 * n * 4 + n * rate // 8
+    ring_hop = {"reduce_mixed_ms": round(hop_mixed, 4), "reduce_mixed_hbm_frac": round(mixed_bytes / (hop_mixed * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "reduce_decompress_ms": round(hop_raw, 4), "reduce_decompress_hbm_frac": round(raw_bytes / (hop_raw * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "note": "compressed incoming chunk + raw local values -> compressed sum / -> fp32 sum"}
+
     # error of the lossy round trip against the original input (reported, not a target)
     back = zc.zc_decompress(c, n, rate)
     err = (back - x).double()
@@ -201,7 +210,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
                                "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
-        "kernels": kernels, "roofline": roofline, "round_trip_error": quality,
+        "kernels": kernels, "ring_hop": ring_hop, "roofline": roofline, "round_trip_error": quality,
     }
 
     if args.sweep:
