@@ -68,9 +68,10 @@ __device__ __forceinline__ zc::Tables stage_decoder_table(uint32_t* lds, const u
 
 // Message buffers are streamed once.  Measured on MI355X: non-temporal 16-byte fp32
 // loads and stores are faster than plain ones (the decompress kernel's 1 GiB of
-// output by a third), non-temporal stores of the narrow stream are no slower, but
-// non-temporal loads of the narrow stream are slower than plain ones.  So: fp32 in
-// and out and stream out are non-temporal, stream in is plain.
+// output by a third); for the narrow compressed stream, non-temporal loads are slower
+// than plain ones, and plain stores let the kernel that consumes the stream next find
+// part of it in the last-level cache.  So fp32 in and out are non-temporal, stream in
+// and out are plain.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -79,6 +80,11 @@ __device__ __forceinline__ T nt_load(const T* p) { return __builtin_nontemporal_
 
 template <class T>
 __device__ __forceinline__ void nt_store(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
+// Stores of the compressed stream are plain: the stream is small and is read again
+// soon (by the next kernel of a ring hop, or by the network), so it may stay cached.
+template <class T>
+__device__ __forceinline__ void stream_store(T* p, T v) { *p = v; }
 
 __device__ __forceinline__ void load_values(const float* in, size_t j, uint32_t (&x)[4]) {
   u32x4 v = nt_load(reinterpret_cast<const u32x4*>(in) + j);
@@ -134,17 +140,17 @@ __device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint3
   uint8_t* p = out + j * B;
   if constexpr (B == 16) {
     u32x4 v = {W[0], W[1], W[2], W[3]};
-    nt_store(reinterpret_cast<u32x4*>(p), v);
+    stream_store(reinterpret_cast<u32x4*>(p), v);
   } else if constexpr (B == 8) {
     u32x2 v = {W[0], W[1]};
-    nt_store(reinterpret_cast<u32x2*>(p), v);
+    stream_store(reinterpret_cast<u32x2*>(p), v);
   } else if constexpr (B % 4 == 0) {
 #pragma unroll
-    for (int i = 0; i < B / 4; ++i) nt_store(reinterpret_cast<uint32_t*>(p) + i, W[i]);
+    for (int i = 0; i < B / 4; ++i) stream_store(reinterpret_cast<uint32_t*>(p) + i, W[i]);
   } else {
     uint16_t* h = reinterpret_cast<uint16_t*>(p);
 #pragma unroll
-    for (int i = 0; i < B / 2; ++i) nt_store(h + i, (uint16_t)(W[i / 2] >> (16 * (i % 2))));
+    for (int i = 0; i < B / 2; ++i) stream_store(h + i, (uint16_t)(W[i / 2] >> (16 * (i % 2))));
   }
 }
 
