@@ -390,3 +390,93 @@ int zc_ref_reduce_decompress(const void *const *in, int k, const float *local, s
   return ZC_REF_OK;
 }
 
+/* ---- half-precision messages ---------------------------------------------- */
+/* The paper does not state the precision of its messages; LLM training traffic
+ * is commonly bf16 or fp16.  These entry points run the same codec on such
+ * buffers: every value is widened to fp32 exactly before compression (both
+ * formats are subsets of fp32), and decompressed values are narrowed with
+ * round-to-nearest-even.  The stream format is unchanged. */
+
+enum { ZC_REF_F32 = 0, ZC_REF_BF16 = 1, ZC_REF_F16 = 2 };
+
+/* bf16 is the upper half of an fp32. */
+static float widen_bf16(uint16_t h) {
+  uint32_t b = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &b, 4);
+  return f;
+}
+
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+static float widen_f16(uint16_t h) {
+  int sign = (h >> 15) & 1, ex = (h >> 10) & 31, frac = h & 1023;
+  float v;
+  if (ex == 0) v = ldexpf((float)frac, -24);                /* zero and subnormals */
+  else if (ex == 31) v = frac ? NAN : INFINITY;
+  else v = ldexpf((float)(frac | 1024), ex - 25);
+  return sign ? -v : v;
+}
+
+float zc_ref_widen(uint16_t h, int dtype) { return dtype == ZC_REF_BF16 ? widen_bf16(h) : widen_f16(h); }
+
+/* Nearest representable value, ties to the even fraction; magnitudes beyond
+ * the largest finite value round to infinity as IEEE prescribes. */
+uint16_t zc_ref_narrow(float f, int dtype) {
+  if (f != f) return dtype == ZC_REF_BF16 ? 0x7FC0 : 0x7E00;
+  uint16_t sign = signbit(f) ? 0x8000 : 0;
+  double a = fabs((double)f);
+  int frac_bits = dtype == ZC_REF_BF16 ? 7 : 10;
+  int emin = dtype == ZC_REF_BF16 ? -126 : -14;   /* exponent of the smallest normal */
+  int emax = dtype == ZC_REF_BF16 ? 127 : 15;
+  int exp_bits_max = dtype == ZC_REF_BF16 ? 255 : 31;
+  if (a == 0.0) return sign;
+  if (isinf(a)) return (uint16_t)(sign | (exp_bits_max << frac_bits));
+  int e;
+  (void)frexp(a, &e);            /* a = m * 2^e, 0.5 <= m < 1 */
+  e -= 1;                        /* a = m' * 2^e, 1 <= m' < 2 */
+  if (e < emin) e = emin;        /* subnormal range: fixed quantum */
+  double q = ldexp(a, frac_bits - e);       /* in units of the last fraction bit: exact */
+  double r = nearbyint(q);                  /* round to nearest, ties to even (default mode) */
+  /* r is in [2^frac_bits, 2^(frac_bits+1)] for normals, [0, 2^frac_bits] for subnormals */
+  long long units = (long long)r;
+  long long biased;
+  if (units >> (frac_bits + 1)) { units >>= 1; e += 1; }    /* rounded up to the next power of two */
+  if (units >> frac_bits) biased = ((long long)(e - emin + 1) << frac_bits) + (units - (1LL << frac_bits));
+  else biased = units;                                      /* subnormal or zero */
+  if (e > emax) biased = (long long)exp_bits_max << frac_bits; /* overflow -> infinity */
+  return (uint16_t)(sign | (uint16_t)biased);
+}
+
+int zc_ref_compress_half(const uint16_t *in, int dtype, size_t n, int rate, void *out, size_t out_cap) {
+  if (dtype != ZC_REF_BF16 && dtype != ZC_REF_F16) return -8;
+  if (!zc_ref_rate_supported(rate)) return ZC_REF_ERR_RATE;
+  if (n == 0) return ZC_REF_OK;
+  if (!in || !out) return ZC_REF_ERR_NULL;
+  if (out_cap < zc_ref_compressed_size(n, rate)) return ZC_REF_ERR_CAPACITY;
+  size_t blocks = (n + 3) / 4;
+  for (size_t j = 0; j < blocks; ++j) {
+    float x[4];
+    for (int i = 0; i < 4; ++i) {
+      size_t idx = 4 * j + (size_t)i;
+      x[i] = zc_ref_widen(in[idx < n ? idx : n - 1], dtype);
+    }
+    encode_block(x, rate, (uint8_t *)out, j * (size_t)(4 * rate));
+  }
+  return ZC_REF_OK;
+}
+
+int zc_ref_decompress_half(const void *in, size_t n, int rate, int dtype, uint16_t *out) {
+  if (dtype != ZC_REF_BF16 && dtype != ZC_REF_F16) return -8;
+  if (!zc_ref_rate_supported(rate)) return ZC_REF_ERR_RATE;
+  if (n == 0) return ZC_REF_OK;
+  if (!in || !out) return ZC_REF_ERR_NULL;
+  size_t blocks = (n + 3) / 4;
+  for (size_t j = 0; j < blocks; ++j) {
+    float x[4];
+    decode_block((const uint8_t *)in, j * (size_t)(4 * rate), rate, x);
+    for (int i = 0; i < 4; ++i)
+      if (4 * j + (size_t)i < n) out[4 * j + (size_t)i] = zc_ref_narrow(x[i], dtype);
+  }
+  return ZC_REF_OK;
+}
+

@@ -58,6 +58,14 @@ def lib():
                                           ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
         L.zc_ref_reduce_decompress.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
                                                ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+        L.zc_ref_widen.argtypes = [ctypes.c_uint16, ctypes.c_int]
+        L.zc_ref_widen.restype = ctypes.c_float
+        L.zc_ref_narrow.argtypes = [ctypes.c_float, ctypes.c_int]
+        L.zc_ref_narrow.restype = ctypes.c_uint16
+        L.zc_ref_compress_half.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
+                                           ctypes.c_void_p, ctypes.c_size_t]
+        L.zc_ref_decompress_half.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -213,3 +221,36 @@ def reduce_decompress(streams, local, n, rate):
     if rc != 0:
         raise ValueError("zc_ref_reduce_decompress failed: %d" % rc)
     return out
+
+
+BF16, F16 = 1, 2
+
+
+def widen(h, dtype):
+    return float(lib().zc_ref_widen(int(h), int(dtype)))
+
+
+def narrow(f, dtype):
+    return int(lib().zc_ref_narrow(float(np.float32(f)), int(dtype)))
+
+
+def compress_half(bits, dtype, rate):
+    """bits: uint16 array of bf16 (dtype=BF16) or fp16 (dtype=F16) bit patterns."""
+    h = np.ascontiguousarray(bits, dtype=np.uint16).reshape(-1)
+    out = np.zeros(compressed_size(h.size, rate), dtype=np.uint8)
+    rc = lib().zc_ref_compress_half(h.ctypes.data, int(dtype), h.size, int(rate), out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError("zc_ref_compress_half failed: %d" % rc)
+    return out
+
+
+def decompress_half(stream, n, rate, dtype):
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    if s.size < compressed_size(n, rate):
+        raise ValueError("stream too short")
+    out = np.zeros(n, dtype=np.uint16)
+    rc = lib().zc_ref_decompress_half(s.ctypes.data, int(n), int(rate), int(dtype), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("zc_ref_decompress_half failed: %d" % rc)
+    return out
+
