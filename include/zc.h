@@ -47,8 +47,12 @@ enum {
   ZC_ERR_CAPACITY = -4, /* out_cap smaller than zc_compressed_size(n, rate) */
   ZC_ERR_K = -5,        /* k outside [1, 16] */
   ZC_ERR_ALIGN = -6,    /* a device pointer is not 16-byte aligned */
-  ZC_ERR_LAUNCH = -7    /* the HIP runtime refused the launch */
+  ZC_ERR_LAUNCH = -7,   /* the HIP runtime refused the launch */
+  ZC_ERR_DTYPE = -8     /* dtype is not ZC_BF16 or ZC_F16 */
 };
+
+/* Element types of a message buffer.  The fp32 calls take no dtype argument. */
+enum zc_dtype { ZC_F32 = 0, ZC_BF16 = 1, ZC_F16 = 2 };
 
 /* Message classes of Table I / Table III. */
 enum zc_class {
@@ -113,6 +117,19 @@ int zc_reduce_mixed(const void* const* d_in, int k, const float* d_local, size_t
  * any d_in[j]. */
 int zc_reduce_decompress(const void* const* d_in, int k, const float* d_local, size_t n, int rate,
                          float* d_out, void* stream);
+
+/* Half-precision messages (the paper does not state its message precision; LLM
+ * training traffic is usually bf16 or fp16).  d_in holds n values of `dtype` (ZC_BF16
+ * or ZC_F16, 2 bytes each).  Every value is widened to fp32, which is exact, and then
+ * compressed exactly as zc_compress would: the stream is the same format and can be fed
+ * to every other call. */
+int zc_compress_half(const void* d_in, int dtype, size_t n, int rate, void* d_out, size_t out_cap,
+                     void* stream);
+
+/* Decompress to n values of `dtype`: what zc_decompress would produce, each value
+ * rounded to the nearest bf16 / fp16 (ties to even; magnitudes beyond the largest
+ * finite value become infinity). */
+int zc_decompress_half(const void* d_in, size_t n, int rate, int dtype, void* d_out, void* stream);
 
 #ifdef __cplusplus
 }

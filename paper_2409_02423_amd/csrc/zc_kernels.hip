@@ -86,29 +86,77 @@ __device__ __forceinline__ void nt_store(T* p, T v) { __builtin_nontemporal_stor
 template <class T>
 __device__ __forceinline__ void stream_store(T* p, T v) { *p = v; }
 
-__device__ __forceinline__ void load_values(const float* in, size_t j, uint32_t (&x)[4]) {
-  u32x4 v = nt_load(reinterpret_cast<const u32x4*>(in) + j);
-  x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+// Element types of a message buffer (values of enum zc_dtype).
+constexpr int kF32 = 0, kBF16 = 1, kF16 = 2;
+
+// Exact widening of a bf16 / fp16 bit pattern to an fp32 bit pattern.
+template <int DT>
+__device__ __forceinline__ uint32_t widen_half(uint32_t h) {
+  if constexpr (DT == kBF16) {
+    return h << 16;
+  } else {
+    const _Float16 v = __builtin_bit_cast(_Float16, (uint16_t)h);
+    return __float_as_uint((float)v);
+  }
+}
+
+// Nearest bf16 / fp16, ties to even.  bf16: add 0x7FFF plus the lowest kept bit to the
+// fp32 pattern and drop 16 bits; a carry into the exponent is the next binade or infinity.
+template <int DT>
+__device__ __forceinline__ uint32_t narrow_half(float f) {
+  if constexpr (DT == kBF16) {
+    const uint32_t b = __float_as_uint(f);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+  } else {
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+  }
+}
+
+// Four values of block j as fp32 bit patterns.
+template <int DT>
+__device__ __forceinline__ void load_values(const void* in, size_t j, uint32_t (&x)[4]) {
+  if constexpr (DT == kF32) {
+    u32x4 v = nt_load(reinterpret_cast<const u32x4*>(in) + j);
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  } else {
+    u32x2 v = nt_load(reinterpret_cast<const u32x2*>(in) + j);
+    x[0] = widen_half<DT>(v.x & 0xFFFFu); x[1] = widen_half<DT>(v.x >> 16);
+    x[2] = widen_half<DT>(v.y & 0xFFFFu); x[3] = widen_half<DT>(v.y >> 16);
+  }
 }
 
 // The ragged last block (n % 4 values) repeats the last value.
-__device__ __forceinline__ void load_values_ragged(const float* in, size_t n, uint32_t (&x)[4]) {
-  const uint32_t* w = reinterpret_cast<const uint32_t*>(in);
+template <int DT>
+__device__ __forceinline__ void load_values_ragged(const void* in, size_t n, uint32_t (&x)[4]) {
   const size_t base = n & ~(size_t)3;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) x[i] = w[base + i < n ? base + i : n - 1];
+  for (int i = 0; i < 4; ++i) {
+    const size_t idx = base + i < n ? base + i : n - 1;
+    if constexpr (DT == kF32) x[i] = reinterpret_cast<const uint32_t*>(in)[idx];
+    else x[i] = widen_half<DT>(reinterpret_cast<const uint16_t*>(in)[idx]);
+  }
 }
 
-__device__ __forceinline__ void store_values(float* out, size_t j, const float (&x)[4]) {
-  u32x4 v = {__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
-  nt_store(reinterpret_cast<u32x4*>(out) + j, v);
+template <int DT>
+__device__ __forceinline__ void store_values(void* out, size_t j, const float (&x)[4]) {
+  if constexpr (DT == kF32) {
+    u32x4 v = {__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+    nt_store(reinterpret_cast<u32x4*>(out) + j, v);
+  } else {
+    u32x2 v = {narrow_half<DT>(x[0]) | narrow_half<DT>(x[1]) << 16, narrow_half<DT>(x[2]) | narrow_half<DT>(x[3]) << 16};
+    nt_store(reinterpret_cast<u32x2*>(out) + j, v);
+  }
 }
 
-__device__ __forceinline__ void store_values_ragged(float* out, size_t n, const float (&x)[4]) {
+template <int DT>
+__device__ __forceinline__ void store_values_ragged(void* out, size_t n, const float (&x)[4]) {
   const size_t base = n & ~(size_t)3;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    if (base + i < n) out[base + i] = x[i];
+    if (base + i < n) {
+      if constexpr (DT == kF32) reinterpret_cast<float*>(out)[base + i] = x[i];
+      else reinterpret_cast<uint16_t*>(out)[base + i] = (uint16_t)narrow_half<DT>(x[i]);
+    }
 }
 
 // Compressed block j: RATE/2 bytes at byte j*RATE/2; bits beyond the block are zero.
@@ -171,8 +219,8 @@ template <int RATE> constexpr int compress_unroll() { return RATE == 4 ? 1 : 4; 
 template <int RATE> constexpr int decompress_unroll() { return RATE == 4 ? 1 : 4; }
 template <int RATE> constexpr int reduce_unroll() { return 4; }
 
-template <int RATE, int U>
-__global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restrict__ in, size_t n,
+template <int RATE, int U, int DT>
+__global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restrict__ in, size_t n,
                                                             uint8_t* __restrict__ out) {
   __shared__ __align__(16) uint32_t enc[kEncWords];
   stage_table<kEncWords>(enc, g_enc_table.v);
@@ -186,14 +234,14 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
   if (t < tiles) {
     uint32_t x[U][4];
 #pragma unroll
-    for (int u = 0; u < U; ++u) load_values(in, t * kTile + u * kThreads + threadIdx.x, x[u]);
+    for (int u = 0; u < U; ++u) load_values<DT>(in, t * kTile + u * kThreads + threadIdx.x, x[u]);
     while (true) {
       const size_t tn = t + gridDim.x;
       const bool more = tn < tiles;
       const size_t next = (more ? tn : t) * kTile + threadIdx.x;
       uint32_t xn[U][4];
 #pragma unroll
-      for (int u = 0; u < U; ++u) load_values(in, next + u * kThreads, xn[u]);
+      for (int u = 0; u < U; ++u) load_values<DT>(in, next + u * kThreads, xn[u]);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         uint32_t W[NW];
@@ -211,21 +259,21 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float* __restr
   for (size_t j = tiles * kTile + (size_t)blockIdx.x * kThreads + threadIdx.x; j < whole;
        j += (size_t)gridDim.x * kThreads) {
     uint32_t x[4], W[NW];
-    load_values(in, j, x);
+    load_values<DT>(in, j, x);
     zc::encode_block<RATE>(x, tab, W, AnyLane());
     store_stream<RATE>(out, j, W);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t x[4], W[NW];
-    load_values_ragged(in, n, x);
+    load_values_ragged<DT>(in, n, x);
     zc::encode_block<RATE>(x, tab, W, AnyLane());
     store_stream<RATE>(out, whole, W);
   }
 }
 
-template <int RATE, int U>
+template <int RATE, int U, int DT>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __restrict__ in, size_t n,
-                                                              float* __restrict__ out) {
+                                                              void* __restrict__ out) {
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
   const zc::Tables tab = stage_decoder_table<RATE>(dec, nullptr);
   __syncthreads();
@@ -249,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
       for (int u = 0; u < U; ++u) {
         float y[4];
         zc::decode_block<RATE>(W[u], tab, y, AnyLane());
-        store_values(out, t * kTile + u * kThreads + threadIdx.x, y);
+        store_values<DT>(out, t * kTile + u * kThreads + threadIdx.x, y);
       }
       if (!more) break;
 #pragma unroll
@@ -265,14 +313,14 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
     float y[4];
     load_stream<RATE>(in, j, W);
     zc::decode_block<RATE>(W, tab, y, AnyLane());
-    store_values(out, j, y);
+    store_values<DT>(out, j, y);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t W[NW];
     float y[4];
     load_stream<RATE>(in, whole, W);
     zc::decode_block<RATE>(W, tab, y, AnyLane());
-    store_values_ragged(out, n, y);
+    store_values_ragged<DT>(out, n, y);
   }
 }
 
@@ -308,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
       for (int i = 0; i < 4; ++i) s[i] += __uint_as_float(loc[i]);
     }
     if constexpr (RAW_OUT) {
-      store_values(out_raw, j, s);
+      store_values<kF32>(out_raw, j, s);
     } else {
       uint32_t x[4], Wo[NW];
 #pragma unroll
@@ -329,7 +377,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
       uint32_t loc[U][4];
       if constexpr (LOCAL) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) load_values(local, t * kTile + u * kThreads + threadIdx.x, loc[u]);
+        for (int u = 0; u < U; ++u) load_values<kF32>(local, t * kTile + u * kThreads + threadIdx.x, loc[u]);
       }
       float s[U][4];
       for (int c = 0; c < k; ++c) {
@@ -371,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
        j += (size_t)gridDim.x * kThreads) {
     float s[4] = {0.f, 0.f, 0.f, 0.f};
     uint32_t loc[4] = {0, 0, 0, 0};
-    if constexpr (LOCAL) load_values(local, j, loc);
+    if constexpr (LOCAL) load_values<kF32>(local, j, loc);
     direct_sum(j, s);
     finish(s, loc, j);
   }
@@ -380,12 +428,12 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
     direct_sum(whole, s);
     if constexpr (LOCAL) {
       uint32_t loc[4];
-      load_values_ragged(local, n, loc);
+      load_values_ragged<kF32>(local, n, loc);
 #pragma unroll
       for (int i = 0; i < 4; ++i) s[i] += __uint_as_float(loc[i]);
     }
     if constexpr (RAW_OUT) {
-      store_values_ragged(out_raw, n, s);
+      store_values_ragged<kF32>(out_raw, n, s);
     } else {
       // the result is compress(sum): the pad repeats the last valid sum
       const int valid = (int)(n & 3);
@@ -480,6 +528,7 @@ const char* zc_strerror(int code) {
     case ZC_ERR_K: return "number of chunks outside [1, 16]";
     case ZC_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case ZC_ERR_LAUNCH: return "kernel launch failed";
+    case ZC_ERR_DTYPE: return "dtype must be ZC_BF16 or ZC_F16";
     default: return "unknown error code";
   }
 }
@@ -502,7 +551,9 @@ size_t zc_compressed_size(size_t n, int rate) {
   return (n / 4 + (n % 4 ? 1 : 0)) * (size_t)(rate / 2);
 }
 
-int zc_compress(const float* d_in, size_t n, int rate, void* d_out, size_t out_cap, void* stream) {
+static int launch_compress(const void* d_in, int dtype, size_t n, int rate, void* d_out, size_t out_cap,
+                           void* stream) {
+  if (dtype != ZC_F32 && dtype != ZC_BF16 && dtype != ZC_F16) return ZC_ERR_DTYPE;
   if (!zc_rate_supported(rate)) return ZC_ERR_RATE;
   if (n == 0) return ZC_OK;
   if (!d_in || !d_out) return ZC_ERR_NULL;
@@ -510,23 +561,62 @@ int zc_compress(const float* d_in, size_t n, int rate, void* d_out, size_t out_c
   if (n > kMaxValues) return ZC_ERR_SIZE;
   if (out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL((compress_kernel<R, compress_unroll<R>()>), dim3(grid_for(n, kCompress, R)), dim3(kThreads), 0, s, d_in, n, static_cast<uint8_t*>(d_out))
+  uint8_t* out = static_cast<uint8_t*>(d_out);
+#define LAUNCH(R, DT)                                                                                            \
+  hipLaunchKernelGGL((compress_kernel<R, compress_unroll<R>(), DT>), dim3(grid_for(n, kCompress, R)),            \
+                     dim3(kThreads), 0, s, d_in, n, out)
+#define CALL(R)                                   \
+  do {                                            \
+    if (dtype == ZC_F32) LAUNCH(R, kF32);         \
+    else if (dtype == ZC_BF16) LAUNCH(R, kBF16);  \
+    else LAUNCH(R, kF16);                         \
+  } while (0)
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
+#undef LAUNCH
   return finish_launch();
 }
 
-int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stream) {
+static int launch_decompress(const void* d_in, size_t n, int rate, int dtype, void* d_out, void* stream) {
+  if (dtype != ZC_F32 && dtype != ZC_BF16 && dtype != ZC_F16) return ZC_ERR_DTYPE;
   if (!zc_rate_supported(rate)) return ZC_ERR_RATE;
   if (n == 0) return ZC_OK;
   if (!d_in || !d_out) return ZC_ERR_NULL;
   if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
   if (n > kMaxValues) return ZC_ERR_SIZE;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL((decompress_kernel<R, decompress_unroll<R>()>), dim3(grid_for(n, kDecompress, R)), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), n, d_out)
+  const uint8_t* in = static_cast<const uint8_t*>(d_in);
+#define LAUNCH(R, DT)                                                                                            \
+  hipLaunchKernelGGL((decompress_kernel<R, decompress_unroll<R>(), DT>), dim3(grid_for(n, kDecompress, R)),      \
+                     dim3(kThreads), 0, s, in, n, d_out)
+#define CALL(R)                                   \
+  do {                                            \
+    if (dtype == ZC_F32) LAUNCH(R, kF32);         \
+    else if (dtype == ZC_BF16) LAUNCH(R, kBF16);  \
+    else LAUNCH(R, kF16);                         \
+  } while (0)
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
+#undef LAUNCH
   return finish_launch();
+}
+
+int zc_compress(const float* d_in, size_t n, int rate, void* d_out, size_t out_cap, void* stream) {
+  return launch_compress(d_in, ZC_F32, n, rate, d_out, out_cap, stream);
+}
+
+int zc_decompress(const void* d_in, size_t n, int rate, float* d_out, void* stream) {
+  return launch_decompress(d_in, n, rate, ZC_F32, d_out, stream);
+}
+
+int zc_compress_half(const void* d_in, int dtype, size_t n, int rate, void* d_out, size_t out_cap, void* stream) {
+  if (dtype != ZC_BF16 && dtype != ZC_F16) return ZC_ERR_DTYPE;
+  return launch_compress(d_in, dtype, n, rate, d_out, out_cap, stream);
+}
+
+int zc_decompress_half(const void* d_in, size_t n, int rate, int dtype, void* d_out, void* stream) {
+  if (dtype != ZC_BF16 && dtype != ZC_F16) return ZC_ERR_DTYPE;
+  return launch_decompress(d_in, n, rate, dtype, d_out, stream);
 }
 
 static int launch_reduce(const void* const* d_in, int k, const float* d_local, size_t n, int rate, void* d_out,

@@ -14,11 +14,13 @@ from . import build as _build
 
 ZC_OK = 0
 ZC_ERR_NULL, ZC_ERR_RATE, ZC_ERR_SIZE, ZC_ERR_CAPACITY = -1, -2, -3, -4
-ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH = -5, -6, -7
+ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH, ZC_ERR_DTYPE = -5, -6, -7, -8
+ZC_F32, ZC_BF16, ZC_F16 = 0, 1, 2
 ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE = range(5)
 
 EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
-           "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress")
+           "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
+           "zc_compress_half", "zc_decompress_half")
 
 _lib = None
 
@@ -57,6 +59,10 @@ def lib():
                                       ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.zc_reduce_decompress.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p,
                                            ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.zc_compress_half.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
+                                       ctypes.c_size_t, ctypes.c_void_p]
+        L.zc_decompress_half.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -204,5 +210,48 @@ def zc_reduce_decompress(d_in, d_local, n, rate, d_out=None, stream=None):
                                     _stream_handle(stream))
     if rc != ZC_OK:
         raise ZcError(rc, "zc_reduce_decompress")
+    return d_out
+
+
+def _half_dtype(t):
+    if t.dtype == torch.bfloat16:
+        return ZC_BF16
+    if t.dtype == torch.float16:
+        return ZC_F16
+    raise TypeError("expected a bfloat16 or float16 tensor")
+
+
+def zc_compress_half(d_in, rate, d_out=None, stream=None):
+    """bfloat16 / float16 CUDA tensor -> uint8 CUDA tensor (same stream format as zc_compress)."""
+    dtype = _half_dtype(d_in)
+    _check_device_tensor(d_in, d_in.dtype, "d_in")
+    n = d_in.numel()
+    if d_out is None:
+        d_out = _new_stream_buffer(n, rate, d_in.device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zc_compress_half(d_in.data_ptr(), dtype, n, int(rate), d_out.data_ptr(), d_out.numel(),
+                                _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_compress_half")
+    return d_out
+
+
+def zc_decompress_half(d_in, n, rate, dtype=None, d_out=None, stream=None):
+    """Compressed stream -> bfloat16 / float16 CUDA tensor; give torch dtype or d_out."""
+    _check_device_tensor(d_in, torch.uint8, "d_in")
+    need = zc_compressed_size(n, rate)
+    if need == 0 and n != 0:
+        raise ZcError(ZC_ERR_RATE, "zc_decompress_half")
+    if d_in.numel() < need:
+        raise ValueError("d_in holds %d bytes, need %d" % (d_in.numel(), need))
+    if d_out is None:
+        d_out = torch.empty(n, dtype=dtype, device=d_in.device)
+    code = _half_dtype(d_out)
+    _check_device_tensor(d_out, d_out.dtype, "d_out")
+    if d_out.numel() < n:
+        raise ValueError("d_out holds %d values, need %d" % (d_out.numel(), n))
+    rc = lib().zc_decompress_half(d_in.data_ptr(), int(n), int(rate), code, d_out.data_ptr(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc_decompress_half")
     return d_out
 

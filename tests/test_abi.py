@@ -41,11 +41,11 @@ def test_sizes_and_policy():
 
 def test_error_strings():
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = zc.zc_strerror(code)
         assert s and s != "unknown error code"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert zc.zc_strerror(-99) == "unknown error code"
 
 
@@ -83,6 +83,15 @@ def test_argument_errors_come_before_any_launch():
     assert L.zc_reduce_decompress(two, 17, good, 16, 8, good, None) == zc.ZC_ERR_K
     assert L.zc_reduce_decompress(two, 2, good, 16, 6, good, None) == zc.ZC_ERR_RATE
     assert L.zc_reduce_decompress(two, 2, None, 0, 8, None, None) == zc.ZC_OK
+    assert L.zc_compress_half(good, 0, 16, 8, good, 100, None) == zc.ZC_ERR_DTYPE
+    assert L.zc_compress_half(good, 3, 16, 8, good, 100, None) == zc.ZC_ERR_DTYPE
+    assert L.zc_compress_half(good, zc.ZC_BF16, 16, 8, good, 15, None) == zc.ZC_ERR_CAPACITY
+    assert L.zc_compress_half(good, zc.ZC_F16, 16, 9, good, 100, None) == zc.ZC_ERR_RATE
+    assert L.zc_compress_half(None, zc.ZC_F16, 16, 8, good, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc_compress_half(None, zc.ZC_F16, 0, 8, None, 0, None) == zc.ZC_OK
+    assert L.zc_decompress_half(good, 16, 8, 0, good, None) == zc.ZC_ERR_DTYPE
+    assert L.zc_decompress_half(good, 16, 8, zc.ZC_BF16, odd, None) == zc.ZC_ERR_ALIGN
+    assert L.zc_decompress_half(good, 16, 8, zc.ZC_F16, None, None) == zc.ZC_ERR_NULL
 
 
 def test_binding_rejects_host_tensors():

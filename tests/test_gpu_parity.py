@@ -245,6 +245,47 @@ def test_full_ring_on_one_share(gpu, oracle):
                          oracle.reduce_decompress([acc_ref], raw[7], n, rate), "ring result")
 
 
+# ---- half-precision messages ---------------------------------------------------------------
+
+def _half_bits(x, name):
+    if name == "f16":
+        with np.errstate(over="ignore"):
+            return x.astype(np.float16).view(np.uint16)
+    return (x.view(np.uint32) >> 16).astype(np.uint16)   # any bf16 pattern is a valid input
+
+
+@pytest.mark.parametrize("name", ["bf16", "f16"])
+def test_half_precision_messages(gpu, oracle, name):
+    import torch
+    tdtype = torch.bfloat16 if name == "bf16" else torch.float16
+    code = oracle.BF16 if name == "bf16" else oracle.F16
+    x = np.concatenate([workloads.gradient_iid(40000), workloads.activation_gelu(30000), workloads.parameters(9003),
+                        workloads.edge_values(3)])
+    x = x[np.abs(x) < 6e4] if name == "f16" else x      # keep fp16 inputs finite
+    h = _half_bits(x, name)
+    n = h.size
+    dh = torch.from_numpy(h.view(np.int16)).cuda().view(tdtype)
+    for rate in RATES:
+        print("half", name, "rate", rate, flush=True)
+        want_c = oracle.compress_half(h, code, rate)
+        got_c = gpu.zc_compress_half(dh, rate)
+        _assert_bytes_equal(_host(got_c), want_c, rate // 2, "compress %s r%d" % (name, rate))
+        want_d = oracle.decompress_half(want_c, n, rate, code)
+        got_d = gpu.zc_decompress_half(got_c, n, rate, dtype=tdtype)
+        got_bits = _host(got_d.view(torch.int16)).view(np.uint16)
+        assert np.array_equal(got_bits, want_d), ("decompress %s r%d" % (name, rate), np.flatnonzero(got_bits != want_d)[:5])
+    # the stream is the ordinary format: the fp32 calls read it, and fp32 streams decode to halves
+    c32 = gpu.zc_compress(_dev(x), 16)
+    want = oracle.decompress_half(oracle.compress(x, 16), x.size, 16, code)
+    got = _host(gpu.zc_decompress_half(c32, x.size, 16, dtype=tdtype).view(torch.int16)).view(np.uint16)
+    assert np.array_equal(got, want)
+    for m in (1, 2, 3, 5, 1027):
+        got_c = gpu.zc_compress_half(dh[:m].clone(), 8)
+        _assert_bytes_equal(_host(got_c), oracle.compress_half(h[:m], code, 8), 4, "ragged %s %d" % (name, m))
+        got = _host(gpu.zc_decompress_half(got_c, m, 8, dtype=tdtype).view(torch.int16)).view(np.uint16)
+        assert np.array_equal(got, oracle.decompress_half(_host(got_c), m, 8, code))
+
+
 # ---- full-size configurations, sampled comparison -------------------------------------------------
 
 def _sample_ranges(blocks, count, length, seed):
