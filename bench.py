@@ -195,6 +195,29 @@ def main():
                 "reduce_decompress_ms": round(hop_raw, 4), "reduce_decompress_hbm_frac": round(raw_bytes / (hop_raw * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "note": "compressed incoming chunk + raw local values -> compressed sum / -> fp32 sum"}
 
+    # the same buffer as a bf16 message (not part of `value`)
+    xh = x.to(torch.bfloat16)
+    yh = torch.empty_like(xh)
+    ch = torch.empty_like(c)
+    half_marks = []
+    for _ in range(12):
+        e = [ev() for _ in range(3)]
+        e[0].record()
+        zc.zc_compress_half(xh, rate, d_out=ch)
+        e[1].record()
+        zc.zc_decompress_half(ch, n, rate, d_out=yh)
+        e[2].record()
+        half_marks.append(e)
+    torch.cuda.synchronize()
+    hb = n * 2 + n * rate // 8
+    hc = float(np.median([m[0].elapsed_time(m[1]) for m in half_marks[2:]]))
+    hd = float(np.median([m[1].elapsed_time(m[2]) for m in half_marks[2:]]))
+    half_precision = {"dtype": "bf16", "compress_ms": round(hc, 4), "decompress_ms": round(hd, 4),
+                      "compress_hbm_frac": round(hb / (hc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "decompress_hbm_frac": round(hb / (hd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "values_per_s_compress": round(n / (hc * 1e-3), 0)}
+    del xh, yh, ch
+
     # error of the lossy round trip against the original input (reported, not a target)
     back = zc.zc_decompress(c, n, rate)
     err = (back - x).double()
@@ -210,7 +233,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
                                "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
-        "kernels": kernels, "ring_hop": ring_hop, "roofline": roofline, "round_trip_error": quality,
+        "kernels": kernels, "ring_hop": ring_hop, "half_precision": half_precision, "roofline": roofline, "round_trip_error": quality,
     }
 
     if args.sweep:
