@@ -1,0 +1,203 @@
+"""Pins for the 2-D (4 x 4 block) reference codec: coefficient order, exponent,
+separable transform against the 1-D basis matrix, range, the 16-coefficient
+embedded coder (closed form per plane, lossless round trip, prefix property,
+brute-force search decoding), a hand-derived block, sizes, ragged edges,
+monotone error."""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2409_02423_amd import workloads
+
+M = (1 << 27) - 1
+FULL = 32 * 31   # no plane costs more than 31 bits
+
+
+@pytest.fixture(scope="module")
+def o2():
+    from oracle import zc2d_ref
+    zc2d_ref.lib()
+    return zc2d_ref
+
+
+def test_order_is_by_total_sequency(o2):
+    o = list(o2.order())
+    assert sorted(o) == list(range(16)) and o[0] == 0 and o[-1] == 15
+    keys = [(v // 4 + v % 4, v // 4) for v in o]
+    assert keys == sorted(keys)
+
+
+def test_exponent_closed_form(o2):
+    e = workloads.edge_values(8)
+    for blk in e[: e.size // 16 * 16].reshape(-1, 16)[::3]:
+        bits = blk.view(np.uint32)
+        F = (bits >> 23) & 0xFF
+        want = int(F.max()) + 1 if F.max() > 0 else (1 if (bits & 0x7FFFFF).any() else 0)
+        assert o2.block_exponent(blk) == want
+
+
+def test_transform_is_exactly_invertible(o2):
+    rng = np.random.default_rng(51)
+    for v in rng.integers(-M, M + 1, size=(4000, 16)):
+        assert np.array_equal(o2.inv_transform(o2.fwd_transform(v)), v)
+    for v in itertools.product([M, -M, 0], repeat=4):          # extreme rows, repeated and mixed
+        for w in ([1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, 0, 0, -1]):
+            blk = np.array([[a * s for a in v] for s in w], dtype=np.int64).reshape(16)
+            t = o2.fwd_transform(blk)
+            assert np.array_equal(o2.inv_transform(t), blk)
+            # every coefficient stays inside what 32 negabinary digits express without wrap-around
+            assert t.astype(np.int64).max() <= 0x55555555 and t.astype(np.int64).min() >= -0xAAAAAAAA
+            assert np.abs(t.astype(np.int64)).max() <= 9 * M + 16
+    for v in rng.integers(-(1 << 31), 1 << 31, size=(2000, 16)):   # wrap-around arithmetic still inverts
+        assert np.array_equal(o2.fwd_transform(o2.inv_transform(v)), v.astype(np.int32))
+
+
+def test_transform_is_separable_basis_matrix(o2):
+    """On multiples of 256 no shift drops a bit in either pass: T = A X A^T with the 1-D matrix A."""
+    A = np.array([[Fraction(1, 4)] * 4,
+                  [Fraction(5, 4), Fraction(1, 4), Fraction(-1, 4), Fraction(-5, 4)],
+                  [Fraction(-1, 2), Fraction(1, 2), Fraction(1, 2), Fraction(-1, 2)],
+                  [Fraction(-1, 4), Fraction(3, 4), Fraction(-3, 4), Fraction(1, 4)]], dtype=object)
+    rng = np.random.default_rng(52)
+    for X in rng.integers(-(1 << 18), 1 << 18, size=(300, 4, 4)) * 256:
+        want = A.dot(X.astype(object)).dot(A.T)
+        got = o2.fwd_transform(X.reshape(16)).reshape(4, 4)
+        assert all(Fraction(int(got[i, j])) == want[i, j] for i in range(4) for j in range(4))
+    c = 12345 * 256
+    assert list(o2.fwd_transform([c] * 16)) == [c] + [0] * 15
+
+
+def _planewise_closed_form(u, ncoef=16):
+    out, n = [], 0
+    for k in range(31, -1, -1):
+        p = [(int(x) >> k) & 1 for x in u]
+        out += p[:n]
+        start = n
+        for j in [j for j in range(n, ncoef) if p[j]]:
+            out.append(1)
+            out += [0] * (j - start)
+            if j < ncoef - 1:
+                out.append(1)
+            start = j + 1
+        if start < ncoef:
+            out.append(0)
+        n = start
+    return out
+
+
+def _random_words(rng, count):
+    w = rng.integers(0, 1 << 32, size=(count, 16), dtype=np.uint64)
+    sh = rng.integers(0, 33, size=(count, 16)).astype(np.uint64)
+    sh = np.minimum(sh + np.arange(16, dtype=np.uint64) // 3, 32)   # later coefficients tend to be smaller
+    return (w >> sh).astype(np.uint32)
+
+
+def test_coder_closed_form_roundtrip_prefix(o2):
+    rng = np.random.default_rng(53)
+    for u in _random_words(rng, 1500):
+        bits, w = o2.encode_planes(u, FULL)
+        want = _planewise_closed_form(u)
+        assert w == len(want) and list(bits[:w]) == want and not bits[w:].any()
+        assert np.array_equal(o2.decode_planes(bits, FULL), u)
+        for b in (1, 8, 24, 56, 120, 248):
+            part, wb = o2.encode_planes(u, b)
+            assert wb == min(b, w) and np.array_equal(part, bits[:b])
+    bits, w = o2.encode_planes(np.zeros(16, np.uint32), FULL)
+    assert w == 32 and not bits.any()
+    bits, w = o2.encode_planes(np.full(16, 0xFFFFFFFF, np.uint32), FULL)
+    assert w == 31 + 31 * 16 and bits[:w].all()
+
+
+def _weight(v):
+    return sum(bin(int(x)).count("1") * (100 + i) for i, x in enumerate(v))
+
+
+def _search_check(o2, tuples, to_words, maxb, full_upto, sample):
+    rng = np.random.default_rng(55)
+    streams = {}
+    for t in tuples:
+        bits, _ = o2.encode_planes(to_words(t), maxb)
+        streams[t] = tuple(int(x) for x in bits)
+    for b in range(0, maxb + 1):
+        groups = {}
+        for t, s in streams.items():
+            groups.setdefault(s[:b], []).append(t)
+        keys = list(groups)
+        if b > full_upto and len(keys) > sample:
+            keys = [keys[i] for i in rng.choice(len(keys), sample, replace=False)]
+        for prefix in keys:
+            best = min(groups[prefix], key=_weight)
+            got = o2.decode_planes(np.array(prefix + (1,) * 4, dtype=np.uint8), b)
+            assert np.array_equal(got, to_words(best)), (b, prefix)
+
+
+def test_decoder_by_brute_force_search(o2):
+    """The decoder returns the lightest tuple whose stream starts with the given prefix
+    (unseen bits zero, an unlocated one at the lowest index still possible)."""
+    # one plane, every pattern of the 16 coefficients; every prefix up to 12 bits, a sample beyond
+    pats = [tuple((p >> i) & 1 for i in range(16)) for p in range(1 << 16)]
+    _search_check(o2, pats, lambda t: np.array(t, dtype=np.uint32) << np.uint32(31), 33, 12, 1500)
+    # two planes, the first five coefficients, every prefix
+    tup = [tuple(t) + (0,) * 11 for t in itertools.product(range(4), repeat=5)]
+    _search_check(o2, tup, lambda t: np.array(t, dtype=np.uint32) << np.uint32(30), 30, 30, 0)
+
+
+def test_hand_derived_block(o2):
+    """Sixteen ones at rate 1: 1 = 0.5 * 2^1, so E = 128; q = 2^26 everywhere; the
+    transform leaves the mean 2^26 and zeros; its negabinary word has digit 26 only.
+    Planes 31..27 are empty (five 0 group bits), plane 26: group bit 1, first locate bit
+    1 (coefficient 0), group bit 0 for the rest: payload bits 0,0,0,0,0,1,1,0 = 0x60."""
+    blk = o2.encode_block(np.ones(16, np.float32), 1)
+    assert list(blk) == [0x80, 0x60]
+    assert np.array_equal(o2.decode_block(blk, 1), np.ones(16, np.float32))
+    assert not o2.encode_block(np.zeros(16, np.float32), 4).any()
+    assert not o2.decode_block(np.zeros(8, np.uint8), 4).view(np.uint32).any()
+
+
+def test_sizes_edges_and_fill(o2):
+    for rate in (1, 2, 4, 8, 16, 32):
+        assert o2.compressed_size(64, 128, rate) == 64 * 128 * rate // 8
+        assert o2.compressed_size(5, 9, rate) == 2 * 3 * 2 * rate
+    assert o2.compressed_size(8, 8, 0) == 0 and o2.compressed_size(8, 8, 33) == 0
+    x = workloads.gradient_lowrank(37, 50).reshape(37, 50)
+    for rate in (2, 4, 8, 16):
+        for rows, cols in ((37, 50), (36, 50), (37, 48), (1, 1), (3, 50), (4, 5)):
+            xs = np.ascontiguousarray(x[:rows, :cols])
+            padded = np.pad(xs, ((0, (-rows) % 4), (0, (-cols) % 4)), mode="edge")
+            c = o2.compress(xs, rate)
+            assert c.size == o2.compressed_size(rows, cols, rate)
+            assert np.array_equal(c, o2.compress(padded, rate))
+            d = o2.decompress(c, rows, cols, rate)
+            assert np.array_equal(d, o2.decompress(c, padded.shape[0], padded.shape[1], rate)[:rows, :cols])
+    # block (bi, bj) sits at byte (bi * blocks_per_row + bj) * 2 * rate and depends on its 16 values only
+    c = o2.compress(x[:36, :48], 8).reshape(9, 12, 16)
+    assert np.array_equal(c[2, 5], o2.encode_block(x[8:12, 20:24].reshape(16), 8))
+
+
+@pytest.mark.parametrize("maker", [lambda: workloads.gradient_iid(1 << 16).reshape(256, 256),
+                                   lambda: workloads.gradient_lowrank(256, 256).reshape(256, 256),
+                                   lambda: workloads.activation_gelu(1 << 16).reshape(128, 512)])
+def test_error_falls_with_rate_and_beats_1d(o2, oracle, maker):
+    x = maker()
+    prev = np.inf
+    for rate in (1, 2, 4, 8, 12, 16, 24, 32):
+        d = o2.decompress(o2.compress(x, rate), x.shape[0], x.shape[1], rate).astype(np.float64)
+        rmse = np.sqrt(np.mean((d - x) ** 2))
+        assert rmse < prev
+        prev = rmse
+        if rate in (4, 8):   # one header per 16 values instead of 4 leaves more bits for data
+            d1 = oracle.decompress(oracle.compress(x.reshape(-1), rate), x.size, rate).astype(np.float64)
+            assert rmse < 0.8 * np.sqrt(np.mean((d1 - x.reshape(-1)) ** 2))
+    assert prev < 1e-6 * x.std()
+
+
+def test_arbitrary_bytes_decode(o2):
+    rng = np.random.default_rng(54)
+    for rate in (2, 4, 8, 16):
+        s = rng.integers(0, 256, size=o2.compressed_size(32, 64, rate), dtype=np.uint8)
+        with np.errstate(all="ignore"):
+            a = o2.decompress(s, 32, 64, rate)
+            b = o2.decompress(s.copy(), 32, 64, rate)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
