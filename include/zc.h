@@ -42,7 +42,7 @@ extern "C" {
 enum {
   ZC_OK = 0,
   ZC_ERR_NULL = -1,     /* a required pointer is NULL */
-  ZC_ERR_RATE = -2,     /* rate not in {4,8,...,32} */
+  ZC_ERR_RATE = -2,     /* rate not in {4,8,...,32} (zc2d_*: not in {2,4,8,16}) */
   ZC_ERR_SIZE = -3,     /* n too large for this build (more than 2^40 values) */
   ZC_ERR_CAPACITY = -4, /* out_cap smaller than zc_compressed_size(n, rate) */
   ZC_ERR_K = -5,        /* k outside [1, 16] */
@@ -130,6 +130,40 @@ int zc_compress_half(const void* d_in, int dtype, size_t n, int rate, void* d_ou
  * rounded to the nearest bf16 / fp16 (ties to even; magnitudes beyond the largest
  * finite value become infinity). */
 int zc_decompress_half(const void* d_in, size_t n, int rate, int dtype, void* d_out, void* stream);
+
+/*
+ * Matrix-shaped messages, format "ZC-2D": the same codec family (Sec. II-A, Sec.
+ * III-B) on blocks of 4 x 4 values, for weight-matrix gradients and [tokens x hidden]
+ * activations, whose structure runs in both directions (the low-rank remark of Sec. I).
+ * A row-major rows x cols fp32 matrix is cut into blocks (bi, bj) = rows 4bi..4bi+3,
+ * columns 4bj..4bj+3, stored in row-major block order, each exactly 16*rate bits =
+ * 2*rate bytes: one header byte (biased shared exponent of the 16 values, 0 = all-zero
+ * block) and 16*rate-8 payload bits from block-floating-point conversion with 27
+ * fraction bits, the lifting transform of ZC-1 along rows and then along columns,
+ * coefficients ordered by total frequency, negabinary mapping and embedded bit-plane
+ * coding over 16 coefficients.  Blocks that stick out of the matrix are filled by
+ * repeating the last row / column; the fill is dropped on decompression.  The
+ * conventions at the top of this file apply (device pointers, 16-byte aligned, stream,
+ * error codes); ZC_ERR_RATE here means a rate outside {2, 4, 8, 16}, ZC_ERR_SIZE a
+ * matrix of more than 2^40 values.  rows == 0 or cols == 0 is valid and does nothing.
+ */
+
+/* 1 if `rate` (bits per value) is supported by the zc2d_* calls: 2, 4, 8, 16. */
+int zc2d_rate_supported(int rate);
+
+/* Bytes of the compressed form of a rows x cols matrix:
+ * ceil(rows/4) * ceil(cols/4) * 2*rate.  0 if the rate is unsupported. */
+size_t zc2d_compressed_size(size_t rows, size_t cols, int rate);
+
+/* Compress the row-major matrix d_in[rows*cols] into
+ * d_out[0..zc2d_compressed_size(rows,cols,rate)).  d_out must not overlap d_in. */
+int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap,
+                  void* stream);
+
+/* Decompress into the row-major matrix d_out[rows*cols].  d_in holds
+ * zc2d_compressed_size(rows,cols,rate) bytes and may contain arbitrary bytes.  d_out
+ * must not overlap d_in. */
+int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -1,11 +1,12 @@
-"""Compile the HIP library (csrc/zc_kernels.hip) for gfx950 into libzc.so next to
-this file.  hipcc cross-compiles without a GPU."""
+"""Compile the HIP library (csrc/zc_kernels.hip, csrc/zc2d_kernels.hip) for gfx950 into
+libzc.so next to this file.  hipcc cross-compiles without a GPU."""
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "zc_kernels.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "zc_codec.h"), os.path.join(HERE, "..", "include", "zc.h")]
+SOURCES = [os.path.join(HERE, "csrc", "zc_kernels.hip"), os.path.join(HERE, "csrc", "zc2d_kernels.hip")]
+DEPS = SOURCES + [os.path.join(HERE, "csrc", "zc_codec.h"), os.path.join(HERE, "csrc", "zc2d_codec.h"),
+                  os.path.join(HERE, "..", "include", "zc.h")]
 LIB = os.path.join(HERE, "libzc.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -25,7 +26,7 @@ def is_stale():
 def build(extra_flags=(), out=None):
     out = out or LIB
     tmp = out + ".tmp.%d" % os.getpid()
-    subprocess.check_call([HIPCC] + FLAGS + list(extra_flags) + [SRC, "-o", tmp])
+    subprocess.check_call([HIPCC] + FLAGS + list(extra_flags) + SOURCES + ["-o", tmp])
     os.replace(tmp, out)
     return out
 

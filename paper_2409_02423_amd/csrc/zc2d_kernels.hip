@@ -1,0 +1,205 @@
+// zc2d_kernels.hip -- gfx950 kernels and C ABI for the 4 x 4 block codec (see include/zc.h).
+//
+// One lane per block of 4 x 4 values, blocks taken in row-major block order with a grid
+// stride, so that the 64 lanes of a wavefront read four contiguous 1 KiB spans (one per
+// matrix row of the block row) and write one contiguous span of 64 * 2*RATE stream bytes.
+// The 16 plane patterns of a block are parked in a per-lane column of LDS (rows of 256
+// lanes, so neighbouring lanes hit neighbouring banks).  No matrix cores: nothing here
+// is a contraction.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/zc.h"
+#include "zc2d_codec.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWorkgroupsPerCU = 16;
+
+struct AnyLane {
+  __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Block (bi, bj) of a rows x cols matrix as fp32 bit patterns; parts that stick out of
+// the matrix repeat the last valid row / column.
+__device__ __forceinline__ void load_block(const float* in, size_t rows, size_t cols, size_t bi, size_t bj, bool fast,
+                                           uint32_t (&x)[16]) {
+  if (fast) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + (4 * bi + r) * cols + 4 * bj));
+      x[4 * r] = v.x; x[4 * r + 1] = v.y; x[4 * r + 2] = v.z; x[4 * r + 3] = v.w;
+    }
+  } else {
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(in);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        size_t rr = 4 * bi + r, cc = 4 * bj + c;
+        rr = rr < rows ? rr : rows - 1;
+        cc = cc < cols ? cc : cols - 1;
+        x[4 * r + c] = w[rr * cols + cc];
+      }
+  }
+}
+
+__device__ __forceinline__ void store_block(float* out, size_t rows, size_t cols, size_t bi, size_t bj, bool fast,
+                                            const float (&y)[16]) {
+  if (fast) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const u32x4 v = {__float_as_uint(y[4 * r]), __float_as_uint(y[4 * r + 1]), __float_as_uint(y[4 * r + 2]),
+                       __float_as_uint(y[4 * r + 3])};
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (4 * bi + r) * cols + 4 * bj));
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const size_t rr = 4 * bi + r, cc = 4 * bj + c;
+        if (rr < rows && cc < cols) out[rr * cols + cc] = y[4 * r + c];
+      }
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void load_words(const uint8_t* p, uint32_t (&W)[NW]) {
+  if constexpr (NW == 1) {
+    W[0] = *reinterpret_cast<const uint32_t*>(p);
+  } else if constexpr (NW == 2) {
+    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+    W[0] = v.x; W[1] = v.y;
+  } else {
+#pragma unroll
+    for (int i = 0; i < NW / 4; ++i) {
+      const u32x4 v = reinterpret_cast<const u32x4*>(p)[i];
+      W[4 * i] = v.x; W[4 * i + 1] = v.y; W[4 * i + 2] = v.z; W[4 * i + 3] = v.w;
+    }
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void store_words(uint8_t* p, const uint32_t (&W)[NW]) {
+  if constexpr (NW == 1) {
+    *reinterpret_cast<uint32_t*>(p) = W[0];
+  } else if constexpr (NW == 2) {
+    const u32x2 v = {W[0], W[1]};
+    *reinterpret_cast<u32x2*>(p) = v;
+  } else {
+#pragma unroll
+    for (int i = 0; i < NW / 4; ++i) {
+      const u32x4 v = {W[4 * i], W[4 * i + 1], W[4 * i + 2], W[4 * i + 3]};
+      reinterpret_cast<u32x4*>(p)[i] = v;
+    }
+  }
+}
+
+template <int RATE>
+__global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __restrict__ in, size_t rows, size_t cols,
+                                                              uint8_t* __restrict__ out) {
+  __shared__ uint32_t planes[16 * kThreads];
+  const zc2d::PlaneStore lds = {planes + threadIdx.x, kThreads};
+  constexpr int NW = zc2d::Traits<RATE>::kWords;
+  const size_t bc = (cols + 3) / 4, br = (rows + 3) / 4, blocks = bc * br;
+  const bool aligned_rows = (cols & 3) == 0;
+  for (size_t b = (size_t)blockIdx.x * kThreads + threadIdx.x; b < blocks; b += (size_t)gridDim.x * kThreads) {
+    const size_t bi = b / bc, bj = b - bi * bc;
+    const bool fast = aligned_rows && 4 * bi + 4 <= rows;
+    uint32_t x[16], W[NW];
+    load_block(in, rows, cols, bi, bj, fast, x);
+    zc2d::encode_block<RATE>(x, lds, W, AnyLane());
+    store_words<NW>(out + b * zc2d::Traits<RATE>::kBlockBytes, W);
+  }
+}
+
+template <int RATE>
+__global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* __restrict__ in, size_t rows,
+                                                                size_t cols, float* __restrict__ out) {
+  __shared__ uint32_t planes[16 * kThreads];
+  const zc2d::PlaneStore lds = {planes + threadIdx.x, kThreads};
+  constexpr int NW = zc2d::Traits<RATE>::kWords;
+  const size_t bc = (cols + 3) / 4, br = (rows + 3) / 4, blocks = bc * br;
+  const bool aligned_rows = (cols & 3) == 0;
+  for (size_t b = (size_t)blockIdx.x * kThreads + threadIdx.x; b < blocks; b += (size_t)gridDim.x * kThreads) {
+    const size_t bi = b / bc, bj = b - bi * bc;
+    const bool fast = aligned_rows && 4 * bi + 4 <= rows;
+    uint32_t W[NW];
+    float y[16];
+    load_words<NW>(in + b * zc2d::Traits<RATE>::kBlockBytes, W);
+    zc2d::decode_block<RATE>(W, lds, y, AnyLane());
+    store_block(out, rows, cols, bi, bj, fast, y);
+  }
+}
+
+int compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+  return cus;
+}
+
+unsigned grid_for(size_t blocks) {
+  const size_t groups = (blocks + kThreads - 1) / kThreads;
+  const size_t cap = (size_t)compute_units() * kWorkgroupsPerCU;
+  return (unsigned)(groups < cap ? groups : cap);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+constexpr size_t kMaxValues = (size_t)1 << 40;
+
+}  // namespace
+
+#define ZC2D_DISPATCH_RATE(rate, CALL) \
+  switch (rate) {                      \
+    case 2: CALL(2); break;            \
+    case 4: CALL(4); break;            \
+    case 8: CALL(8); break;            \
+    case 16: CALL(16); break;          \
+    default: return ZC_ERR_RATE;       \
+  }
+
+extern "C" {
+
+int zc2d_rate_supported(int rate) { return rate == 2 || rate == 4 || rate == 8 || rate == 16; }
+
+size_t zc2d_compressed_size(size_t rows, size_t cols, int rate) {
+  if (!zc2d_rate_supported(rate)) return 0;
+  return ((rows + 3) / 4) * ((cols + 3) / 4) * (size_t)(2 * rate);
+}
+
+int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap, void* stream) {
+  if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
+  if (rows == 0 || cols == 0) return ZC_OK;
+  if (!d_in || !d_out) return ZC_ERR_NULL;
+  if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
+  if (out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
+  const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(R) hipLaunchKernelGGL(compress2d_kernel<R>, dim3(grid_for(blocks)), dim3(kThreads), 0, s, d_in, rows, cols, static_cast<uint8_t*>(d_out))
+  ZC2D_DISPATCH_RATE(rate, CALL)
+#undef CALL
+  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+
+int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream) {
+  if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
+  if (rows == 0 || cols == 0) return ZC_OK;
+  if (!d_in || !d_out) return ZC_ERR_NULL;
+  if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
+  const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(R) hipLaunchKernelGGL(decompress2d_kernel<R>, dim3(grid_for(blocks)), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), rows, cols, d_out)
+  ZC2D_DISPATCH_RATE(rate, CALL)
+#undef CALL
+  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -522,7 +522,7 @@ const char* zc_strerror(int code) {
   switch (code) {
     case ZC_OK: return "ok";
     case ZC_ERR_NULL: return "null pointer";
-    case ZC_ERR_RATE: return "unsupported rate (use a multiple of 4 between 4 and 32)";
+    case ZC_ERR_RATE: return "unsupported rate (a multiple of 4 between 4 and 32; 2, 4, 8 or 16 for the 4 x 4 block codec)";
     case ZC_ERR_SIZE: return "buffer too large";
     case ZC_ERR_CAPACITY: return "output capacity smaller than zc_compressed_size(n, rate)";
     case ZC_ERR_K: return "number of chunks outside [1, 16]";

@@ -20,7 +20,8 @@ ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE 
 
 EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
-           "zc_compress_half", "zc_decompress_half")
+           "zc_compress_half", "zc_decompress_half",
+           "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress")
 
 _lib = None
 
@@ -63,6 +64,13 @@ def lib():
                                        ctypes.c_size_t, ctypes.c_void_p]
         L.zc_decompress_half.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p]
+        L.zc2d_rate_supported.argtypes = [ctypes.c_int]
+        L.zc2d_compressed_size.restype = ctypes.c_size_t
+        L.zc2d_compressed_size.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int]
+        L.zc2d_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
+                                    ctypes.c_size_t, ctypes.c_void_p]
+        L.zc2d_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
+                                      ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -255,3 +263,50 @@ def zc_decompress_half(d_in, n, rate, dtype=None, d_out=None, stream=None):
         raise ZcError(rc, "zc_decompress_half")
     return d_out
 
+
+
+def zc2d_rate_supported(rate):
+    return bool(lib().zc2d_rate_supported(int(rate)))
+
+
+def zc2d_compressed_size(rows, cols, rate):
+    return int(lib().zc2d_compressed_size(int(rows), int(cols), int(rate)))
+
+
+def zc2d_compress(d_in, rate, d_out=None, stream=None):
+    """2-D fp32 CUDA tensor (rows x cols, row-major) -> uint8 CUDA tensor in format ZC-2D."""
+    _check_device_tensor(d_in, torch.float32, "d_in")
+    if d_in.dim() != 2:
+        raise TypeError("d_in must be a matrix")
+    rows, cols = d_in.shape
+    if d_out is None:
+        size = zc2d_compressed_size(rows, cols, rate)
+        if size == 0 and rows * cols != 0:
+            raise ZcError(ZC_ERR_RATE, "zc2d_compressed_size")
+        d_out = torch.empty(size, dtype=torch.uint8, device=d_in.device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zc2d_compress(d_in.data_ptr(), rows, cols, int(rate), d_out.data_ptr(), d_out.numel(),
+                             _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_compress")
+    return d_out
+
+
+def zc2d_decompress(d_in, rows, cols, rate, d_out=None, stream=None):
+    """uint8 CUDA tensor in format ZC-2D -> fp32 CUDA tensor of shape (rows, cols)."""
+    _check_device_tensor(d_in, torch.uint8, "d_in")
+    need = zc2d_compressed_size(rows, cols, rate)
+    if need == 0 and rows * cols != 0:
+        raise ZcError(ZC_ERR_RATE, "zc2d_decompress")
+    if d_in.numel() < need:
+        raise ValueError("d_in holds %d bytes, need %d" % (d_in.numel(), need))
+    if d_out is None:
+        d_out = torch.empty((rows, cols), dtype=torch.float32, device=d_in.device)
+    _check_device_tensor(d_out, torch.float32, "d_out")
+    if d_out.numel() < rows * cols:
+        raise ValueError("d_out holds %d values, need %d" % (d_out.numel(), rows * cols))
+    rc = lib().zc2d_decompress(d_in.data_ptr(), int(rows), int(cols), int(rate), d_out.data_ptr(),
+                               _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_decompress")
+    return d_out

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "zc.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(zc_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(zc(?:2d)?_[a-z_]+)\s*\(", text))
     assert declared == set(zc.EXPORTS)
     L = ctypes.CDLL(zc.library_path()) if os.path.exists(zc.library_path()) else zc.lib()
     for name in declared:
@@ -100,3 +100,29 @@ def test_binding_rejects_host_tensors():
         zc.zc_compress(torch.zeros(8), 8)
     with pytest.raises(TypeError):
         zc.zc_decompress(torch.zeros(8, dtype=torch.uint8), 8, 8)
+
+
+def test_2d_sizes_and_argument_errors():
+    for rate in range(-2, 36):
+        ok = rate in (2, 4, 8, 16)
+        assert zc.zc2d_rate_supported(rate) == ok
+        assert zc.zc2d_compressed_size(64, 128, rate) == (64 * 128 * rate // 8 if ok else 0)
+    assert zc.zc2d_compressed_size(0, 7, 4) == 0 and zc.zc2d_compressed_size(7, 0, 4) == 0
+    assert zc.zc2d_compressed_size(1, 1, 2) == 4 and zc.zc2d_compressed_size(5, 9, 4) == 2 * 3 * 8
+    assert zc.zc2d_compressed_size(6144, 43690, 4) == 1536 * 10923 * 8
+    L = zc.lib()
+    good, odd = 0x10000, 0x10004  # never dereferenced: every call fails validation first
+    assert L.zc2d_compress(good, 4, 4, 12, good, 100, None) == zc.ZC_ERR_RATE
+    assert L.zc2d_compress(None, 0, 9, 4, None, 0, None) == zc.ZC_OK
+    assert L.zc2d_compress(None, 9, 0, 4, None, 0, None) == zc.ZC_OK
+    assert L.zc2d_compress(None, 4, 4, 4, good, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc2d_compress(good, 4, 4, 4, None, 100, None) == zc.ZC_ERR_NULL
+    assert L.zc2d_compress(odd, 4, 4, 4, good, 100, None) == zc.ZC_ERR_ALIGN
+    assert L.zc2d_compress(good, 4, 4, 4, odd, 100, None) == zc.ZC_ERR_ALIGN
+    assert L.zc2d_compress(good, 1 << 21, 1 << 20, 4, good, 1 << 62, None) == zc.ZC_ERR_SIZE
+    assert L.zc2d_compress(good, 5, 9, 4, good, 47, None) == zc.ZC_ERR_CAPACITY
+    assert L.zc2d_decompress(good, 4, 4, 3, good, None) == zc.ZC_ERR_RATE
+    assert L.zc2d_decompress(None, 0, 0, 4, None, None) == zc.ZC_OK
+    assert L.zc2d_decompress(None, 4, 4, 4, good, None) == zc.ZC_ERR_NULL
+    assert L.zc2d_decompress(good, 4, 4, 4, odd, None) == zc.ZC_ERR_ALIGN
+    assert L.zc2d_decompress(good, 1 << 41, 1, 4, good, None) == zc.ZC_ERR_SIZE

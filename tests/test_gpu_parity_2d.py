@@ -1,0 +1,192 @@
+"""GPU parity for the 4 x 4 block codec (zc2d_* calls of include/zc.h) against the CPU
+reference oracle/zc2d_ref, bit for bit: streams as bytes, matrices as fp32 bit patterns."""
+import numpy as np
+import pytest
+
+from paper_2409_02423_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+RATES = (2, 4, 8, 16)
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2409_02423_amd import zc
+    zc.lib()
+    return zc
+
+
+@pytest.fixture(scope="module")
+def ref():
+    from oracle import zc2d_ref
+    zc2d_ref.lib()
+    return zc2d_ref
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _host(t):
+    return t.cpu().numpy()
+
+
+def _same_bytes(got, want, rate, what):
+    got, want = np.asarray(got).reshape(-1), np.asarray(want).reshape(-1)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero(got != want)
+        raise AssertionError("%s: %d bytes differ, first at byte %d (block %d)" %
+                             (what, bad.size, bad[0], bad[0] // (2 * rate)))
+
+
+def _same_floats(got, want, what):
+    g, w = np.asarray(got).view(np.uint32), np.asarray(want).view(np.uint32)
+    assert g.shape == w.shape, (what, g.shape, w.shape)
+    if not np.array_equal(g, w):
+        bad = np.argwhere(g != w)
+        raise AssertionError("%s: %d values differ, first at %s: got %08x want %08x" %
+                             (what, len(bad), tuple(bad[0]), g[tuple(bad[0])], w[tuple(bad[0])]))
+
+
+def _round_trip(gpu, ref, x, rate, what):
+    rows, cols = x.shape
+    want_c = ref.compress(x, rate)
+    got_c = gpu.zc2d_compress(_dev(x), rate)
+    _same_bytes(_host(got_c), want_c, rate, "compress " + what)
+    want_d = ref.decompress(want_c, rows, cols, rate)
+    got_d = gpu.zc2d_decompress(got_c, rows, cols, rate)
+    _same_floats(_host(got_d), want_d, "decompress " + what)
+
+
+def _matrix(rows, cols, seed, kind="lowrank"):
+    if kind == "lowrank":
+        return workloads.gradient_lowrank(rows, cols, config=2, index=seed).reshape(rows, cols)
+    if kind == "act":
+        return workloads.activation_gelu(rows * cols, config=3, index=seed).reshape(rows, cols)
+    return workloads.gradient_iid(rows * cols, config=1, index=seed).reshape(rows, cols)
+
+
+@pytest.mark.parametrize("rate", RATES)
+def test_edge_values(gpu, ref, rate):
+    """Zeros, signed zeros, subnormals, extremes and mixed magnitudes, in three shapes so
+    that the same values fall into different blocks."""
+    v = workloads.edge_values(33)
+    for cols in (4, 12, 52):
+        rows = v.size // cols
+        print("2d edge values rate", rate, "shape", rows, cols, flush=True)
+        _round_trip(gpu, ref, v[: rows * cols].reshape(rows, cols).copy(), rate, "edge %dx%d r%d" % (rows, cols, rate))
+
+
+@pytest.mark.parametrize("rate", RATES)
+def test_arbitrary_bytes_decode_alike(gpu, ref, rate):
+    print("2d arbitrary bytes rate", rate, flush=True)
+    rng = np.random.default_rng(300 + rate)
+    rows, cols = 203, 410      # ragged in both directions
+    size = ((rows + 3) // 4) * ((cols + 3) // 4) * 2 * rate
+    s = rng.integers(0, 256, size=size, dtype=np.uint8)
+    s[: size // 3] &= rng.integers(0, 256, size=size // 3, dtype=np.uint8)
+    with np.errstate(all="ignore"):
+        want = ref.decompress(s, rows, cols, rate)
+    got = gpu.zc2d_decompress(_dev(s), rows, cols, rate)
+    _same_floats(_host(got), want, "arbitrary bytes r%d" % rate)
+
+
+SHAPES = [(1, 1), (1, 9), (9, 1), (3, 5), (4, 4), (5, 4), (4, 5), (8, 1024), (7, 1030), (1029, 7), (256, 1024),
+          (258, 1026), (1023, 64), (64, 1023), (1025, 1028)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_small_and_ragged_shapes(gpu, ref, shape):
+    rows, cols = shape
+    x = _matrix(rows, cols, seed=rows % 7)
+    for rate in RATES:
+        print("2d shape", shape, "rate", rate, flush=True)
+        _round_trip(gpu, ref, x, rate, "%dx%d r%d" % (rows, cols, rate))
+
+
+@pytest.mark.parametrize("kind", ["lowrank", "act", "iid"])
+def test_more_blocks_than_one_pass_of_the_grid(gpu, ref, kind):
+    """4096 x 4100 values = 1.05 M blocks (the widest grid covers 1.05 M lanes only when
+    256 * 16 workgroups are resident), and 2052 x 8200 with a ragged last block row."""
+    for rows, cols in ((4096, 4100), (2050, 8202)):
+        x = _matrix(rows, cols, seed=3, kind=kind)
+        for rate in (4, 8):
+            print("2d large", kind, rows, cols, "rate", rate, flush=True)
+            _round_trip(gpu, ref, x, rate, "%s %dx%d r%d" % (kind, rows, cols, rate))
+
+
+def test_only_the_stated_bytes_are_written(gpu, ref):
+    import torch
+    rows, cols, rate = 37, 1021, 4
+    x = _matrix(rows, cols, seed=5)
+    size = gpu.zc2d_compressed_size(rows, cols, rate)
+    out = torch.full((size + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    gpu.zc2d_compress(_dev(x), rate, d_out=out)
+    h = _host(out)
+    _same_bytes(h[:size], ref.compress(x, rate), rate, "canary compress")
+    assert (h[size:] == 0xA5).all()
+    dec = torch.full((rows * cols + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    gpu.zc2d_decompress(out[:size], rows, cols, rate, d_out=dec)
+    hd = _host(dec)
+    _same_floats(hd[: rows * cols].reshape(rows, cols), ref.decompress(h[:size], rows, cols, rate), "canary decompress")
+    assert np.isnan(hd[rows * cols:]).all()
+
+
+def test_empty_and_errors_on_device(gpu):
+    import torch
+    x = torch.zeros((8, 8), dtype=torch.float32, device="cuda")
+    assert gpu.zc2d_compress(torch.zeros((0, 8), dtype=torch.float32, device="cuda"), 4).numel() == 0
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_compress(x, 12)
+    assert e.value.code == gpu.ZC_ERR_RATE
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_compress(x, 4, d_out=torch.zeros(31, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == gpu.ZC_ERR_CAPACITY
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_compress(x.reshape(-1)[1:33].reshape(4, 8), 4)
+    assert e.value.code == gpu.ZC_ERR_ALIGN
+    torch.cuda.synchronize()
+
+
+def test_runs_on_a_side_stream(gpu, ref):
+    import torch
+    x = _matrix(512, 2048, seed=2)
+    s = torch.cuda.Stream()
+    dx = _dev(x)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        c = gpu.zc2d_compress(dx, 8, stream=s)
+        d = gpu.zc2d_decompress(c, 512, 2048, 8, stream=s)
+    s.synchronize()
+    want_c = ref.compress(x, 8)
+    _same_bytes(_host(c), want_c, 8, "side stream compress")
+    _same_floats(_host(d), ref.decompress(want_c, 512, 2048, 8), "side stream decompress")
+
+
+def test_full_size_gradient_matrix_sampled(gpu, ref):
+    """The matrix the benchmark times the 2-D calls on (8192 x 32768 = 2^28 values with the
+    low-rank structure of configuration 2), at the rates it is timed at; the reference
+    recomputes sampled bands of block rows."""
+    rows, cols = 8192, 32768
+    x = workloads.gradient_lowrank(rows, cols, config=2, index=0).reshape(rows, cols)
+    dx = _dev(x)
+    bc = (cols + 3) // 4
+    rng = np.random.default_rng(77)
+    bands = sorted(set([0, rows // 4 - 1] + [int(b) for b in rng.integers(0, rows // 4, size=6)]))
+    for rate in (2, 4, 8):
+        dc = gpu.zc2d_compress(dx, rate)
+        dd = gpu.zc2d_decompress(dc, rows, cols, rate)
+        for bi in bands:
+            print("2d full size rate", rate, "block row", bi, flush=True)
+            xs = x[4 * bi: 4 * bi + 4]
+            want_c = ref.compress(xs, rate)
+            got_c = _host(dc[bi * bc * 2 * rate: (bi + 1) * bc * 2 * rate])
+            _same_bytes(got_c, want_c, rate, "full r%d block row %d" % (rate, bi))
+            _same_floats(_host(dd[4 * bi: 4 * bi + 4]), ref.decompress(want_c, 4, cols, rate),
+                         "full r%d rows from %d" % (rate, 4 * bi))
+        del dc, dd
