@@ -216,7 +216,38 @@ def main():
                       "compress_hbm_frac": round(hb / (hc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                       "decompress_hbm_frac": round(hb / (hd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                       "values_per_s_compress": round(n / (hc * 1e-3), 0)}
+
+    # 4 x 4 blocks on a matrix of the same size and structure (not part of `value`)
     del xh, yh, ch
+    m_rows, m_cols = 8192, 32768
+    xm = torch.from_numpy(workloads.gradient_lowrank(m_rows, m_cols, config=2, index=0)).to(dev).reshape(m_rows, m_cols)
+    ym = y.reshape(m_rows, m_cols)
+    blocks_4x4 = {"matrix": "%dx%d rank-8 + noise" % (m_rows, m_cols)}
+    for r2 in (4, 8):
+        cm = torch.empty(zc.zc2d_compressed_size(m_rows, m_cols, r2), dtype=torch.uint8, device=dev)
+        m2 = []
+        for _ in range(12):
+            e = [ev() for _ in range(3)]
+            e[0].record()
+            zc.zc2d_compress(xm, r2, d_out=cm)
+            e[1].record()
+            zc.zc2d_decompress(cm, m_rows, m_cols, r2, d_out=ym)
+            e[2].record()
+            m2.append(e)
+        torch.cuda.synchronize()
+        tc = float(np.median([m[0].elapsed_time(m[1]) for m in m2[2:]]))
+        td = float(np.median([m[1].elapsed_time(m[2]) for m in m2[2:]]))
+        mb = 4 * n + cm.numel()
+        rel2 = float(((ym - xm).double().pow(2).mean() / xm.double().pow(2).mean()).sqrt())
+        one = zc.zc_decompress(zc.zc_compress(xm.reshape(-1), r2), n, r2)
+        rel1 = float(((one - xm.reshape(-1)).double().pow(2).mean() / xm.double().pow(2).mean()).sqrt())
+        del one, cm
+        blocks_4x4["rate_%d" % r2] = {
+            "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+            "compress_hbm_frac": round(mb / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "decompress_hbm_frac": round(mb / (td * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "relative_rms_error": round(rel2, 5), "relative_rms_error_blocks_of_4": round(rel1, 5)}
+    del xm, ym
 
     # error of the lossy round trip against the original input (reported, not a target)
     back = zc.zc_decompress(c, n, rate)
@@ -233,7 +264,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
                                "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
-        "kernels": kernels, "ring_hop": ring_hop, "half_precision": half_precision, "roofline": roofline, "round_trip_error": quality,
+        "kernels": kernels, "ring_hop": ring_hop, "half_precision": half_precision, "blocks_4x4": blocks_4x4, "roofline": roofline, "round_trip_error": quality,
     }
 
     if args.sweep:

@@ -8,15 +8,25 @@
 // 16*RATE-8 bits behind a one-byte exponent header.
 //
 // How the bit-plane code is computed here:
-//   * the 16 coefficient words are bit-transposed (two 16 x 16 transposes done at once
-//     in the two halves of 32-bit registers), so that plane k is one 16-bit pattern;
-//     the patterns are parked in a per-lane column of LDS, from which the plane loop
-//     (uniform over the wavefront) fetches one pattern per step;
-//   * within a plane the newly significant coefficients are found with count-trailing-
-//     zeros instead of bit by bit: each costs a group bit, its run of zeros and (unless
-//     it is the last coefficient) a one;
-//   * a budget cut inside a run places the decoded one after the zeros read so far,
-//     which is the lowest index still possible.
+//   * the words are aligned so that the first non-empty plane is bit 31, and their upper
+//     halves are bit-transposed (a 16 x 16 transpose on eight registers that hold two
+//     16-bit rows each), so that each of the first 16 planes is one 16-bit pattern in a
+//     register; the lower halves are transposed only if some lane of the wavefront gets
+//     that far within its budget, which low rates rarely do;
+//   * the plane loop is unrolled, uniform over the wavefront, and ends when no lane has
+//     budget left;
+//   * encoder: the group tests of a plane are computed without a loop.  In the stream
+//     the newly significant coefficient of index p (counted from the first coefficient
+//     not yet significant) and rank j (1-based) ends its token at bit p + j, and every
+//     token starts one bit after the previous one ended, so the code is the pattern
+//     with each one moved up by its rank (two look-ups in a 256-entry table) plus that
+//     word shifted by one;
+//   * decoder: a table indexed by the next 10 stream bits decodes all the tokens that
+//     lie whole within them; it is used when its result stays inside the budget and
+//     below the last coefficient (whose token has no closing one), otherwise one token
+//     is decoded by count-trailing-zeros with the limits applied.  A budget cut inside
+//     a run places the decoded one after the zeros read so far, which is the lowest
+//     index still possible.
 #ifndef ZC2D_CODEC_H
 #define ZC2D_CODEC_H
 
@@ -56,46 +66,81 @@ constexpr Order build_order() {
 }
 constexpr Order kOrder = build_order();
 
-// ---- 16 x 16 bit transpose in both halves of sixteen 32-bit words --------------------
-// In: word c, bit b (b < 16) and bit 16 + b.  Out: word b, bit c = in word c bit b, and
-// bit 16 + c = in word c bit 16 + b.  Four rounds of block swaps between word pairs.
-ZC_DEV constexpr void transpose16(uint32_t (&a)[16]) {
-  constexpr uint32_t mask[4] = {0x00FF00FFu, 0x0F0F0F0Fu, 0x33333333u, 0x55555555u};
+// ---- 16 x 16 bit transpose on eight words ----------------------------------------------
+// Row r of a 16 x 16 bit matrix sits in half r >> 3 of word r & 7 (half 0 = bits 0..15).
+// The transpose leaves the matrix in the same arrangement, so it is its own inverse.
+ZC_DEV constexpr void transpose_halves(uint32_t (&a)[8]) {
+  // swap the 8 x 8 quadrants: bits 8..15 of row r with bits 0..7 of row r + 8
+#pragma unroll
+  for (int w = 0; w < 8; ++w) a[w] = (a[w] & 0xFF0000FFu) | ((a[w] & 0x0000FF00u) << 8) | ((a[w] >> 8) & 0x0000FF00u);
+  constexpr uint32_t mask[3] = {0x0F0F0F0Fu, 0x33333333u, 0x55555555u};
   int m = 0;
 #pragma unroll
-  for (int j = 8; j >= 1; j >>= 1, ++m)
+  for (int j = 4; j >= 1; j >>= 1, ++m)
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      if ((r & j) == 0) {
-        const uint32_t lo = a[r], hi = a[r + j];
-        a[r] = (lo & mask[m]) | ((hi & mask[m]) << j);
-        a[r + j] = ((lo >> j) & mask[m]) | (hi & ~mask[m]);
+    for (int w = 0; w < 8; ++w)
+      if ((w & j) == 0) {
+        const uint32_t lo = a[w], hi = a[w + j];
+        a[w] = (lo & mask[m]) | ((hi & mask[m]) << j);
+        a[w + j] = ((lo >> j) & mask[m]) | (hi & ~mask[m]);
       }
+}
+
+// ---- tables --------------------------------------------------------------------------
+// Encoder: v[c] has, for each one of c at position p with 1-based rank j, bit p + j set.
+struct ExpandTable { uint32_t v[256]; };
+constexpr ExpandTable build_expand_table() {
+  ExpandTable t{};
+  for (int c = 0; c < 256; ++c) {
+    uint32_t e = 0;
+    int rank = 0;
+    for (int p = 0; p < 8; ++p)
+      if ((c >> p) & 1) { ++rank; e |= 1u << (p + rank); }
+    t.v[c] = e;
+  }
+  return t;
+}
+
+// Decoder: entry for the next kLookahead stream bits at the start of a group test, with
+// all the tokens (one, zeros, one) that lie whole within them and a closing zero if it
+// follows: bits 0..9 the ones, as positions past the current coefficient; bits 12..15
+// how many coefficients were passed; bits 16..19 how many stream bits were used; bit 20
+// set if the closing zero was among them.
+constexpr int kLookahead = 10;
+struct TokenTable { uint32_t v[1 << kLookahead]; };
+constexpr TokenTable build_token_table() {
+  TokenTable t{};
+  for (uint32_t s = 0; s < (1u << kLookahead); ++s) {
+    uint32_t ones = 0, passed = 0, used = 0, closed = 0;
+    while (used < (uint32_t)kLookahead) {
+      if (((s >> used) & 1u) == 0u) { closed = 1; ++used; break; }
+      uint32_t z = 0;
+      while (used + 1 + z < (uint32_t)kLookahead && ((s >> (used + 1 + z)) & 1u) == 0u) ++z;
+      if (used + 1 + z >= (uint32_t)kLookahead) break;   // the closing one is out of sight
+      ones |= 1u << (passed + z);
+      passed += z + 1;
+      used += z + 2;
+    }
+    t.v[s] = ones | passed << 12 | used << 16 | closed << 20;
+  }
+  return t;
 }
 
 namespace selfcheck {
 constexpr bool transpose_ok() {
-  uint32_t a[16] = {}, ref[16] = {};
+  uint32_t a[8] = {}, ref[8] = {};
   uint32_t s = 0x9E3779B9u;
-  for (int c = 0; c < 16; ++c) { s = s * 1664525u + 1013904223u; a[c] = s; }
-  for (int c = 0; c < 16; ++c)
-    for (int b = 0; b < 16; ++b) {
-      ref[b] |= ((a[c] >> b) & 1u) << c;
-      ref[b] |= ((a[c] >> (16 + b)) & 1u) << (16 + c);
-    }
-  transpose16(a);
-  for (int c = 0; c < 16; ++c)
-    if (a[c] != ref[c]) return false;
+  for (int w = 0; w < 8; ++w) { s = s * 1664525u + 1013904223u; a[w] = s; }
+  for (int r = 0; r < 16; ++r)
+    for (int b = 0; b < 16; ++b)
+      ref[b & 7] |= ((a[r & 7] >> (16 * (r >> 3) + b)) & 1u) << (16 * (b >> 3) + r);
+  transpose_halves(a);
+  for (int w = 0; w < 8; ++w)
+    if (a[w] != ref[w]) return false;
   return true;
 }
 static_assert(transpose_ok(), "16 x 16 bit transpose");
 }  // namespace selfcheck
-
-// Per-lane column of sixteen 32-bit rows in LDS: row r of lane l at plane_rows[r * stride + l].
-struct PlaneStore {
-  uint32_t* rows;   // already offset to this lane
-  int stride;       // lanes per row
-};
 
 // ---- forward ---------------------------------------------------------------------------
 
@@ -126,8 +171,31 @@ ZC_DEV void forward_transform(const uint32_t (&x)[16], uint32_t& E, uint32_t (&u
   for (int c = 0; c < 16; ++c) u[c] = ((uint32_t)q[kOrder.v[c]] + 0xAAAAAAAAu) ^ 0xAAAAAAAAu;
 }
 
+// One plane of the embedded code.  pat: the plane's bit of each coefficient; n: how many
+// leading coefficients are significant; left: budget.  Appends to the window W.
+template <int NW>
+ZC_DEV void encode_plane(uint32_t pat, const uint32_t* expand, uint32_t (&W)[NW], uint32_t& n, uint32_t& left) {
+  // coefficients already significant: their bits as they are
+  const uint32_t vlen = umin(n, left);
+  zc::shift_in<NW>(W, pat, vlen);
+  left -= vlen;
+  // the rest: ends of the tokens, then their starts one bit after the previous end
+  const uint32_t rest = pat >> n;
+  const uint32_t lo = expand[rest & 0xFFu], hi = expand[rest >> 8];
+  const uint32_t ends = lo | hi << (8u + (uint32_t)__builtin_popcount(rest & 0xFFu));
+  const uint32_t last = 31u - count_leading_zeros(ends);      // wraps to -1 if there is none
+  const uint32_t starts = ((ends << 1) & ((1u << (last & 31u)) - 1u)) | umin(ends, 1u);
+  uint32_t len = last + 2u;              // up to the last end, and the closing group bit 0
+  if (pat >> 15) len -= 2u;              // the last coefficient needs neither its end nor a closing bit
+  if (n == 16u) len = 0u;                // (when n is 16 the bit tested above was not a new one)
+  const uint32_t glen = umin(len, left);
+  zc::shift_in<NW>(W, ends | starts, glen);
+  left -= glen;
+  n = umax(n, 32u - count_leading_zeros(pat));
+}
+
 template <int RATE, class AnyActive>
-ZC_DEV void encode_block(const uint32_t (&x)[16], PlaneStore lds, uint32_t (&W)[Traits<RATE>::kWords],
+ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32_t (&W)[Traits<RATE>::kWords],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
   constexpr int kMaxPlanes = Traits<RATE>::kPayloadBits < 32 ? Traits<RATE>::kPayloadBits : 32;
@@ -140,43 +208,30 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], PlaneStore lds, uint32_t (&W)[
   const int32_t avail = Traits<RATE>::kPayloadBits - (int32_t)lead;
   uint32_t left = avail > 0 ? (uint32_t)avail : 0u;
 #pragma unroll
-  for (int c = 0; c < 16; ++c) u[c] <<= (lead & 31u);   // top plane to bit 31
-  transpose16(u);   // u[r]: plane r in the low half, plane 16 + r in the high half
-#pragma unroll
-  for (int r = 0; r < 16; ++r) lds.rows[r * lds.stride] = u[r];
+  for (int c = 0; c < 16; ++c) u[c] <<= (lead & 31u);   // first non-empty plane to bit 31
 #pragma unroll
   for (int j = 0; j < NW; ++j) W[j] = 0;
   uint32_t n = 0;
-#pragma unroll 1
-  for (int t = 0; t < kMaxPlanes; ++t) {
-    if (!any_lane_active(left > 0)) break;
-    const int k = 31 - t;
-    const uint32_t row = lds.rows[(k & 15) * lds.stride];
-    const uint32_t pat = (k & 16) ? row >> 16 : row & 0xFFFFu;
-    // coefficients already significant: their bits as they are
-    const uint32_t vlen = umin(n, left);
-    zc::shift_in<NW>(W, pat, vlen);
-    left -= vlen;
-    // the rest: one group test per newly significant coefficient
-    uint32_t rest = pat >> n, i = n, code = 0, len = 0;
-    while (any_lane_active(rest != 0u)) {
-      if (rest != 0u) {
-        const uint32_t z = count_trailing_zeros(rest);
-        code |= 1u << len;   // the group holds a one
-        len += 1u + z;       // z zeros on the way to it
-        if (i + z < 15u) {   // the one itself, unless it is the last coefficient
-          code |= 1u << len;
-          len += 1u;
-        }
-        rest >>= z + 1u;
-        i += z + 1u;
-      }
+  uint32_t h[8];
+#pragma unroll
+  for (int w = 0; w < 8; ++w) h[w] = (u[w] >> 16) | (u[w + 8] & 0xFFFF0000u);
+  transpose_halves(h);
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
+    const int b = 15 - t;
+    encode_plane<NW>((b >> 3) ? h[b & 7] >> 16 : h[b & 7] & 0xFFFFu, expand, W, n, left);
+  }
+  if (kMaxPlanes > 16 && any_lane_active(left > 0)) {
+#pragma unroll
+    for (int w = 0; w < 8; ++w) h[w] = (u[w] & 0xFFFFu) | (u[w + 8] << 16);
+    transpose_halves(h);
+#pragma unroll
+    for (int t = 16; t < 32; ++t) {
+      if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
+      const int b = 31 - t;
+      encode_plane<NW>((b >> 3) ? h[b & 7] >> 16 : h[b & 7] & 0xFFFFu, expand, W, n, left);
     }
-    if (i < 16u) len += 1u;  // the closing group bit 0
-    const uint32_t glen = umin(len, left);
-    zc::shift_in<NW>(W, code, glen);
-    left -= glen;
-    n = i;
   }
   zc::shift_right<NW>(W, (uint32_t)(32 * NW - Traits<RATE>::kBlockBits) + left);
   W[0] |= E;
@@ -197,8 +252,45 @@ ZC_DEV void inverse_transform(uint32_t (&u)[16], uint32_t E, float (&out)[16]) {
   for (int i = 0; i < 16; ++i) out[i] = __builtin_ldexpf((float)q[i], ex);
 }
 
+// One plane of the embedded code, read from the bottom of the window W.  Returns the
+// plane's bit of each coefficient.
+template <int NW, class AnyActive>
+ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t& n, uint32_t& left,
+                             AnyActive any_lane_active) {
+  const uint32_t vlen = umin(n, left);
+  uint32_t pat = W[0] & ((1u << vlen) - 1u);
+  zc::shift_out<NW>(W, vlen);
+  left -= vlen;
+  uint32_t i = n;
+  bool open = true;
+  for (;;) {
+    const bool active = open && i < 16u && left > 0u;
+    if (!any_lane_active(active)) break;
+    // all the tokens that lie whole in the next bits, if the limits cannot matter to them
+    const uint32_t e = token[W[0] & ((1u << kLookahead) - 1u)];
+    const uint32_t t_used = (e >> 16) & 15u, t_passed = (e >> 12) & 15u;
+    const bool fast = active && t_used != 0u && t_used <= left && i + t_passed <= 15u;
+    // one token with the limits applied: zeros up to the one; the run ends at the last
+    // coefficient or at the budget
+    const uint32_t group = W[0] & 1u;
+    const uint32_t room = umin(15u - i, left - 1u);
+    const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
+    const bool one = active && group != 0u;
+    const uint32_t s_used = one ? 1u + z + (z < room ? 1u : 0u) : (active ? 1u : 0u);
+    const uint32_t used = fast ? t_used : s_used;
+    const uint32_t ones = fast ? (e & 0x3FFu) : (one ? 1u << z : 0u);
+    pat |= ones << (i & 15u);
+    i += fast ? t_passed : (one ? z + 1u : 0u);
+    open = fast ? ((e >> 20) & 1u) == 0u : (active ? group != 0u : open);
+    zc::shift_out<NW>(W, used);
+    left -= used;
+  }
+  n = i;
+  return pat;
+}
+
 template <int RATE, class AnyActive>
-ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], PlaneStore lds, float (&out)[16],
+ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* token, float (&out)[16],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
   constexpr int kPayload = Traits<RATE>::kPayloadBits;
@@ -220,47 +312,38 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], PlaneStore lds, fl
   uint32_t left = (uint32_t)kPayload - lead;
   if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
   zc::shift_right<NW>(W, lead + 8u);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) lds.rows[r * lds.stride] = 0u;
   uint32_t n = 0;
-#pragma unroll 1
-  for (int t = 0; t < kMaxPlanes; ++t) {
-    if (!any_lane_active(left > 0)) break;
-    const uint32_t vlen = umin(n, left);
-    uint32_t pat = W[0] & ((1u << vlen) - 1u);
-    zc::shift_out<NW>(W, vlen);
-    left -= vlen;
-    uint32_t i = n;
-    bool open = true;
-    while (any_lane_active(open && i < 16u && left > 0u)) {
-      uint32_t used = 0;
-      if (open && i < 16u && left > 0u) {
-        const uint32_t group = W[0] & 1u;
-        used = 1u;
-        if (!group) {
-          open = false;
-        } else {
-          // zeros up to the one; the run ends at the last coefficient or at the budget
-          const uint32_t room = umin(15u - i, left - 1u);
-          const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
-          used += z + (z < room ? 1u : 0u);
-          i += z;
-          pat |= 1u << i;
-          i += 1u;
-        }
-      }
-      zc::shift_out<NW>(W, used);
-      left -= used;
-    }
-    n = i;
-    const int k = 31 - t;
-    uint32_t* row = lds.rows + (k & 15) * lds.stride;
-    *row |= (k & 16) ? pat << 16 : pat;
-  }
-  uint32_t u[16];
+  uint32_t h[8], u[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) u[r] = lds.rows[r * lds.stride];
-  transpose16(u);
+  for (int w = 0; w < 8; ++w) h[w] = 0u;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
+    const int b = 15 - t;
+    h[b & 7] |= decode_plane<NW>(token, W, n, left, any_lane_active) << (16 * (b >> 3));
+  }
+  transpose_halves(h);
+#pragma unroll
+  for (int w = 0; w < 8; ++w) {
+    u[w] = h[w] << 16;
+    u[w + 8] = h[w] & 0xFFFF0000u;
+  }
+  if (kMaxPlanes > 16 && any_lane_active(left > 0)) {
+#pragma unroll
+    for (int w = 0; w < 8; ++w) h[w] = 0u;
+#pragma unroll
+    for (int t = 16; t < 32; ++t) {
+      if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
+      const int b = 31 - t;
+      h[b & 7] |= decode_plane<NW>(token, W, n, left, any_lane_active) << (16 * (b >> 3));
+    }
+    transpose_halves(h);
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+      u[w] |= h[w] & 0xFFFFu;
+      u[w + 8] |= h[w] >> 16;
+    }
+  }
 #pragma unroll
   for (int c = 0; c < 16; ++c) u[c] >>= (lead & 31u);   // nothing was decoded if lead >= 32
   inverse_transform(u, E, out);

@@ -3,11 +3,12 @@
 // One lane per block of 4 x 4 values, blocks taken in row-major block order with a grid
 // stride, so that the 64 lanes of a wavefront read four contiguous 1 KiB spans (one per
 // matrix row of the block row) and write one contiguous span of 64 * 2*RATE stream bytes.
-// The 16 plane patterns of a block are parked in a per-lane column of LDS (rows of 256
-// lanes, so neighbouring lanes hit neighbouring banks).  No matrix cores: nothing here
-// is a contraction.
+// A block lives in registers from load to store; LDS holds only the coder's look-up table
+// (1 KiB for the encoder, 4 KiB for the decoder).  No matrix cores: nothing here is a
+// contraction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/zc.h"
 #include "zc2d_codec.h"
@@ -15,7 +16,19 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kWorkgroupsPerCU = 16;
+
+__device__ const zc2d::ExpandTable g_expand = zc2d::build_expand_table();
+__device__ const zc2d::TokenTable g_token = zc2d::build_token_table();
+
+// Copy a table of WORDS 32-bit words to LDS, 16 bytes per lane and step.
+template <int WORDS>
+__device__ __forceinline__ void stage_table(const uint32_t* __restrict__ src, uint32_t* dst) {
+  static_assert(WORDS % 4 == 0, "table size");
+  for (int i = threadIdx.x; i < WORDS / 4; i += kThreads)
+    reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(src)[i];
+  __syncthreads();
+}
+constexpr int kWorkgroupsPerCU = 16;   // ZC2D_WORKGROUPS_PER_CU overrides this for tuning runs
 
 struct AnyLane {
   __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
@@ -103,8 +116,8 @@ __device__ __forceinline__ void store_words(uint8_t* p, const uint32_t (&W)[NW])
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __restrict__ in, size_t rows, size_t cols,
                                                               uint8_t* __restrict__ out) {
-  __shared__ uint32_t planes[16 * kThreads];
-  const zc2d::PlaneStore lds = {planes + threadIdx.x, kThreads};
+  __shared__ __attribute__((aligned(16))) uint32_t expand[256];
+  stage_table<256>(g_expand.v, expand);
   constexpr int NW = zc2d::Traits<RATE>::kWords;
   const size_t bc = (cols + 3) / 4, br = (rows + 3) / 4, blocks = bc * br;
   const bool aligned_rows = (cols & 3) == 0;
@@ -113,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __res
     const bool fast = aligned_rows && 4 * bi + 4 <= rows;
     uint32_t x[16], W[NW];
     load_block(in, rows, cols, bi, bj, fast, x);
-    zc2d::encode_block<RATE>(x, lds, W, AnyLane());
+    zc2d::encode_block<RATE>(x, expand, W, AnyLane());
     store_words<NW>(out + b * zc2d::Traits<RATE>::kBlockBytes, W);
   }
 }
@@ -121,8 +134,8 @@ __global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __res
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* __restrict__ in, size_t rows,
                                                                 size_t cols, float* __restrict__ out) {
-  __shared__ uint32_t planes[16 * kThreads];
-  const zc2d::PlaneStore lds = {planes + threadIdx.x, kThreads};
+  __shared__ __attribute__((aligned(16))) uint32_t token[1 << zc2d::kLookahead];
+  stage_table<(1 << zc2d::kLookahead)>(g_token.v, token);
   constexpr int NW = zc2d::Traits<RATE>::kWords;
   const size_t bc = (cols + 3) / 4, br = (rows + 3) / 4, blocks = bc * br;
   const bool aligned_rows = (cols & 3) == 0;
@@ -132,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* _
     uint32_t W[NW];
     float y[16];
     load_words<NW>(in + b * zc2d::Traits<RATE>::kBlockBytes, W);
-    zc2d::decode_block<RATE>(W, lds, y, AnyLane());
+    zc2d::decode_block<RATE>(W, token, y, AnyLane());
     store_block(out, rows, cols, bi, bj, fast, y);
   }
 }
@@ -144,9 +157,21 @@ int compute_units() {
   return cus;
 }
 
+int workgroups_per_cu() {
+  static int forced = -1;
+  if (forced < 0) {
+    forced = 0;
+    if (const char* e = getenv("ZC2D_WORKGROUPS_PER_CU")) {
+      const int v = atoi(e);
+      if (v >= 1 && v <= 4096) forced = v;
+    }
+  }
+  return forced > 0 ? forced : kWorkgroupsPerCU;
+}
+
 unsigned grid_for(size_t blocks) {
   const size_t groups = (blocks + kThreads - 1) / kThreads;
-  const size_t cap = (size_t)compute_units() * kWorkgroupsPerCU;
+  const size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu();
   return (unsigned)(groups < cap ? groups : cap);
 }
 

@@ -129,6 +129,37 @@ def edge_values(seed=7):
     return np.concatenate([fixed, rnd, loc, sub]).astype(np.float32)
 
 
+def structured_blocks_4x4(seed=7, count=512):
+    """4 x 4 blocks (an array of shape [blocks, 16], row-major blocks) with the shapes
+    that stress a block coder: constant blocks, one non-zero value per block, pure
+    checkerboards and stripes, ramps, a smooth block plus one outlier, and blocks whose
+    values differ only in their last bits; each kind `count` times at magnitudes spread
+    over the whole exponent range."""
+    r = np.random.Generator(np.random.PCG64(BASE_SEED + 9500 + seed))
+    mag = lambda: np.exp2(r.integers(-130, 120, size=(count, 1))).astype(np.float32)
+    base = lambda: (1.0 + r.random((count, 1))).astype(np.float32) * np.where(r.random((count, 1)) < 0.5, -1, 1).astype(np.float32)
+    ii, jj = np.meshgrid(np.arange(4), np.arange(4), indexing="ij")
+    kinds = []
+    kinds.append(np.repeat(base() * mag(), 16, axis=1))                                  # constant
+    one = np.zeros((count, 16), dtype=np.float32)
+    one[np.arange(count), r.integers(0, 16, size=count)] = (base() * mag())[:, 0]
+    kinds.append(one)                                                                    # one value
+    checker = ((-1.0) ** (ii + jj)).reshape(1, 16).astype(np.float32)
+    kinds.append(checker * base() * mag())                                               # checkerboard
+    kinds.append(((-1.0) ** ii).reshape(1, 16).astype(np.float32) * base() * mag())      # row stripes
+    kinds.append(((-1.0) ** jj).reshape(1, 16).astype(np.float32) * base() * mag())      # column stripes
+    ramp = (r.standard_normal((count, 1)) * ii.reshape(1, 16) + r.standard_normal((count, 1)) * jj.reshape(1, 16)
+            + r.standard_normal((count, 1))).astype(np.float32)
+    kinds.append(ramp * mag())                                                           # planes
+    smooth = np.repeat(base(), 16, axis=1) * mag()
+    smooth[np.arange(count), r.integers(0, 16, size=count)] *= np.float32(-37.0)
+    kinds.append(smooth)                                                                 # outlier
+    near = (np.repeat(base(), 16, axis=1).view(np.uint32) ^ r.integers(0, 4, size=(count, 16)).astype(np.uint32))
+    kinds.append(near.view(np.float32) * mag())                                          # last bits differ
+    out = np.concatenate(kinds).astype(np.float32)
+    return np.where(np.isfinite(out), out, np.float32(1.0)).astype(np.float32)
+
+
 # --- the five benchmark configurations ------------------------------------
 
 CONFIGS = {

@@ -6,20 +6,22 @@
 
 namespace {
 auto always = [](bool p) { return p; };
+constexpr zc2d::ExpandTable kExpand = zc2d::build_expand_table();
+constexpr zc2d::TokenTable kToken = zc2d::build_token_table();
 
 template <int RATE>
 void enc(const float* x, uint8_t* out) {
-  uint32_t b[16], W[zc2d::Traits<RATE>::kWords], rows[16];
+  uint32_t b[16], W[zc2d::Traits<RATE>::kWords];
   std::memcpy(b, x, 64);
-  zc2d::encode_block<RATE>(b, zc2d::PlaneStore{rows, 1}, W, always);
+  zc2d::encode_block<RATE>(b, kExpand.v, W, always);
   std::memcpy(out, W, zc2d::Traits<RATE>::kBlockBytes);
 }
 template <int RATE>
 void dec(const uint8_t* in, float* x) {
-  uint32_t W[zc2d::Traits<RATE>::kWords], rows[16];
+  uint32_t W[zc2d::Traits<RATE>::kWords];
   std::memcpy(W, in, zc2d::Traits<RATE>::kBlockBytes);
   float o[16];
-  zc2d::decode_block<RATE>(W, zc2d::PlaneStore{rows, 1}, o, always);
+  zc2d::decode_block<RATE>(W, kToken.v, o, always);
   std::memcpy(x, o, 64);
 }
 }  // namespace

@@ -83,6 +83,16 @@ def test_edge_values(gpu, ref, rate):
 
 
 @pytest.mark.parametrize("rate", RATES)
+def test_structured_blocks(gpu, ref, rate):
+    """Constant, one-hot, checkerboard, striped, planar, outlier and nearly equal blocks at
+    magnitudes over the whole exponent range, laid out as a matrix 36 blocks wide."""
+    b = workloads.structured_blocks_4x4(11, 288)            # 8 kinds x 288 blocks
+    x = b.reshape(-1, 36, 4, 4).transpose(0, 2, 1, 3).reshape(-1, 144).copy()
+    print("2d structured blocks rate", rate, "shape", x.shape, flush=True)
+    _round_trip(gpu, ref, x, rate, "structured r%d" % rate)
+
+
+@pytest.mark.parametrize("rate", RATES)
 def test_arbitrary_bytes_decode_alike(gpu, ref, rate):
     print("2d arbitrary bytes rate", rate, flush=True)
     rng = np.random.default_rng(300 + rate)

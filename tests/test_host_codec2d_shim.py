@@ -40,7 +40,7 @@ def _blocks():
     e = workloads.edge_values(13)
     parts = [e[: e.size // 16 * 16], workloads.gradient_iid(1 << 14), workloads.activation_gelu(1 << 14),
              workloads.adam_second_moments(1 << 12), workloads.gradient_lowrank(64, 128), smooth,
-             np.repeat(workloads.parameters(256), 16)]
+             np.repeat(workloads.parameters(256), 16), workloads.structured_blocks_4x4(3, 256).reshape(-1)]
     return np.concatenate(parts).astype(np.float32).reshape(-1, 16)
 
 
