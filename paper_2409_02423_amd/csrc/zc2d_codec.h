@@ -261,29 +261,29 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
   uint32_t pat = W[0] & ((1u << vlen) - 1u);
   zc::shift_out<NW>(W, vlen);
   left -= vlen;
-  uint32_t i = n;
-  bool open = true;
+  // i: first coefficient not yet known to be significant; watch: the same while group
+  // tests remain, 16 once the closing zero has been read
+  uint32_t i = n, watch = n;
   for (;;) {
-    const bool active = open && i < 16u && left > 0u;
+    const bool active = watch < 16u && left > 0u;
     if (!any_lane_active(active)) break;
-    // all the tokens that lie whole in the next bits, if the limits cannot matter to them
-    const uint32_t e = token[W[0] & ((1u << kLookahead) - 1u)];
-    const uint32_t t_used = (e >> 16) & 15u, t_passed = (e >> 12) & 15u;
-    const bool fast = active && t_used != 0u && t_used <= left && i + t_passed <= 15u;
-    // one token with the limits applied: zeros up to the one; the run ends at the last
-    // coefficient or at the budget
-    const uint32_t group = W[0] & 1u;
-    const uint32_t room = umin(15u - i, left - 1u);
-    const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
-    const bool one = active && group != 0u;
-    const uint32_t s_used = one ? 1u + z + (z < room ? 1u : 0u) : (active ? 1u : 0u);
-    const uint32_t used = fast ? t_used : s_used;
-    const uint32_t ones = fast ? (e & 0x3FFu) : (one ? 1u << z : 0u);
-    pat |= ones << (i & 15u);
-    i += fast ? t_passed : (one ? z + 1u : 0u);
-    open = fast ? ((e >> 20) & 1u) == 0u : (active ? group != 0u : open);
-    zc::shift_out<NW>(W, used);
-    left -= used;
+    if (active) {
+      // all the tokens that lie whole in the next bits, if the limits cannot matter to them
+      const uint32_t e = token[W[0] & ((1u << kLookahead) - 1u)];
+      const uint32_t t_used = (e >> 16) & 15u, t_passed = (e >> 12) & 15u;
+      const bool fast = t_used != 0u && t_used <= left && i + t_passed <= 15u;
+      // otherwise one token with the limits applied (its group bit is a one, or the table
+      // would have served): zeros up to the one; the run ends at the last coefficient or
+      // at the budget
+      const uint32_t room = umin(15u - i, left - 1u);
+      const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
+      const uint32_t used = fast ? t_used : 1u + z + (z < room ? 1u : 0u);
+      pat |= (fast ? (e & 0x3FFu) : 1u << z) << i;
+      i += fast ? t_passed : z + 1u;
+      watch = (fast && (e >> 20) != 0u) ? 16u : i;
+      zc::shift_out<NW>(W, used);
+      left -= used;
+    }
   }
   n = i;
   return pat;

@@ -37,46 +37,78 @@ struct AnyLane {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Block (bi, bj) of a rows x cols matrix as fp32 bit patterns; parts that stick out of
-// the matrix repeat the last valid row / column.
-__device__ __forceinline__ void load_block(const float* in, size_t rows, size_t cols, size_t bi, size_t bj, bool fast,
-                                           uint32_t (&x)[16]) {
-  if (fast) {
+// Shape of the matrix and of the walk over its blocks; the same for every lane.
+struct Walk {
+  size_t rows, cols;
+  size_t bc, blocks;        // blocks per block row, blocks in all
+  size_t stride;            // lanes in the grid: a lane's next block is `stride` blocks on
+  size_t step_bi, step_bj;  // stride / bc, stride % bc
+};
+
+// A lane's place in the walk.  Advancing costs additions only: no division per block.
+struct Cursor {
+  size_t b, bi, bj;   // block index, block row, block column
+  size_t first;       // index of the block's first value, (4 * bi) * cols + 4 * bj
+
+  __device__ __forceinline__ void start(const Walk& w, size_t b0) {
+    b = b0;
+    bi = b0 / w.bc;
+    bj = b0 - bi * w.bc;
+    first = 4 * bi * w.cols + 4 * bj;
+  }
+  __device__ __forceinline__ void advance(const Walk& w) {
+    b += w.stride;
+    bi += w.step_bi;
+    bj += w.step_bj;
+    first += 4 * (w.step_bi * w.cols + w.step_bj);
+    if (bj >= w.bc) {
+      bj -= w.bc;
+      bi += 1;
+      first += 4 * w.cols - 4 * w.bc;
+    }
+  }
+  // all 16 values inside the matrix and every row of the block 16-byte aligned
+  __device__ __forceinline__ bool whole(const Walk& w) const { return (w.cols & 3) == 0 && 4 * bi + 4 <= w.rows; }
+};
+
+// The block under the cursor as fp32 bit patterns; parts that stick out of the matrix
+// repeat the last valid row / column.
+__device__ __forceinline__ void load_block(const float* in, const Walk& w, const Cursor& c, uint32_t (&x)[16]) {
+  if (c.whole(w)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + (4 * bi + r) * cols + 4 * bj));
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + c.first + r * w.cols));
       x[4 * r] = v.x; x[4 * r + 1] = v.y; x[4 * r + 2] = v.z; x[4 * r + 3] = v.w;
     }
   } else {
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(in);
+    const uint32_t* bits = reinterpret_cast<const uint32_t*>(in);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        size_t rr = 4 * bi + r, cc = 4 * bj + c;
-        rr = rr < rows ? rr : rows - 1;
-        cc = cc < cols ? cc : cols - 1;
-        x[4 * r + c] = w[rr * cols + cc];
+      for (int q = 0; q < 4; ++q) {
+        size_t rr = 4 * c.bi + r, cc = 4 * c.bj + q;
+        rr = rr < w.rows ? rr : w.rows - 1;
+        cc = cc < w.cols ? cc : w.cols - 1;
+        x[4 * r + q] = bits[rr * w.cols + cc];
       }
   }
 }
 
-__device__ __forceinline__ void store_block(float* out, size_t rows, size_t cols, size_t bi, size_t bj, bool fast,
-                                            const float (&y)[16]) {
-  if (fast) {
+__device__ __forceinline__ void store_block(float* out, const Walk& w, const Cursor& c, const float (&y)[16]) {
+  if (c.whole(w)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const u32x4 v = {__float_as_uint(y[4 * r]), __float_as_uint(y[4 * r + 1]), __float_as_uint(y[4 * r + 2]),
                        __float_as_uint(y[4 * r + 3])};
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (4 * bi + r) * cols + 4 * bj));
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + c.first + r * w.cols));
     }
   } else {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const size_t rr = 4 * bi + r, cc = 4 * bj + c;
-        if (rr < rows && cc < cols) out[rr * cols + cc] = y[4 * r + c];
+      for (int q = 0; q < 4; ++q) {
+        const size_t rr = 4 * c.bi + r, cc = 4 * c.bj + q;
+        if (rr < w.rows && cc < w.cols) out[rr * w.cols + cc] = y[4 * r + q];
       }
   }
 }
@@ -114,39 +146,64 @@ __device__ __forceinline__ void store_words(uint8_t* p, const uint32_t (&W)[NW])
 }
 
 template <int RATE>
-__global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __restrict__ in, size_t rows, size_t cols,
+__global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __restrict__ in, Walk w,
                                                               uint8_t* __restrict__ out) {
   __shared__ __attribute__((aligned(16))) uint32_t expand[256];
   stage_table<256>(g_expand.v, expand);
   constexpr int NW = zc2d::Traits<RATE>::kWords;
-  const size_t bc = (cols + 3) / 4, br = (rows + 3) / 4, blocks = bc * br;
-  const bool aligned_rows = (cols & 3) == 0;
-  for (size_t b = (size_t)blockIdx.x * kThreads + threadIdx.x; b < blocks; b += (size_t)gridDim.x * kThreads) {
-    const size_t bi = b / bc, bj = b - bi * bc;
-    const bool fast = aligned_rows && 4 * bi + 4 <= rows;
-    uint32_t x[16], W[NW];
-    load_block(in, rows, cols, bi, bj, fast, x);
+  const size_t b0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (b0 >= w.blocks) return;
+  Cursor cur;
+  cur.start(w, b0);
+  uint32_t x[16];
+  load_block(in, w, cur, x);
+  // The first block has to have arrived before the loop starts: with loads still in flight
+  // at its entry, every pass would wait for its own prefetch as well (loads return in order).
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  for (;;) {
+    // The loads of the lane's next block, if it has one, are issued before its current
+    // block is coded.
+    Cursor next = cur;
+    next.advance(w);
+    const bool more = next.b < w.blocks;
+    uint32_t xn[16], W[NW];
+    if (more) load_block(in, w, next, xn);
     zc2d::encode_block<RATE>(x, expand, W, AnyLane());
-    store_words<NW>(out + b * zc2d::Traits<RATE>::kBlockBytes, W);
+    store_words<NW>(out + cur.b * zc2d::Traits<RATE>::kBlockBytes, W);
+    if (!more) break;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = xn[i];
+    cur = next;
   }
 }
 
 template <int RATE>
-__global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* __restrict__ in, size_t rows,
-                                                                size_t cols, float* __restrict__ out) {
+__global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* __restrict__ in, Walk w,
+                                                                float* __restrict__ out) {
   __shared__ __attribute__((aligned(16))) uint32_t token[1 << zc2d::kLookahead];
   stage_table<(1 << zc2d::kLookahead)>(g_token.v, token);
   constexpr int NW = zc2d::Traits<RATE>::kWords;
-  const size_t bc = (cols + 3) / 4, br = (rows + 3) / 4, blocks = bc * br;
-  const bool aligned_rows = (cols & 3) == 0;
-  for (size_t b = (size_t)blockIdx.x * kThreads + threadIdx.x; b < blocks; b += (size_t)gridDim.x * kThreads) {
-    const size_t bi = b / bc, bj = b - bi * bc;
-    const bool fast = aligned_rows && 4 * bi + 4 <= rows;
-    uint32_t W[NW];
+  const size_t b0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (b0 >= w.blocks) return;
+  Cursor cur;
+  cur.start(w, b0);
+  uint32_t W[NW];
+  load_words<NW>(in + cur.b * zc2d::Traits<RATE>::kBlockBytes, W);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), for the same reason as in the compress kernel
+  for (;;) {
+    Cursor next = cur;
+    next.advance(w);
+    const bool more = next.b < w.blocks;
+    if (!more) next = cur;
+    uint32_t Wn[NW];
+    load_words<NW>(in + next.b * zc2d::Traits<RATE>::kBlockBytes, Wn);   // the next block's stream, ahead of time
     float y[16];
-    load_words<NW>(in + b * zc2d::Traits<RATE>::kBlockBytes, W);
     zc2d::decode_block<RATE>(W, token, y, AnyLane());
-    store_block(out, rows, cols, bi, bj, fast, y);
+    store_block(out, w, cur, y);
+    if (!more) break;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) W[i] = Wn[i];
+    cur = next;
   }
 }
 
@@ -173,6 +230,18 @@ unsigned grid_for(size_t blocks) {
   const size_t groups = (blocks + kThreads - 1) / kThreads;
   const size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu();
   return (unsigned)(groups < cap ? groups : cap);
+}
+
+Walk walk_for(size_t rows, size_t cols, unsigned grid) {
+  Walk w;
+  w.rows = rows;
+  w.cols = cols;
+  w.bc = (cols + 3) / 4;
+  w.blocks = ((rows + 3) / 4) * w.bc;
+  w.stride = (size_t)grid * kThreads;
+  w.step_bi = w.stride / w.bc;
+  w.step_bj = w.stride % w.bc;
+  return w;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -207,7 +276,9 @@ int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d
   if (out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
   const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL(compress2d_kernel<R>, dim3(grid_for(blocks)), dim3(kThreads), 0, s, d_in, rows, cols, static_cast<uint8_t*>(d_out))
+  const unsigned grid = grid_for(blocks);
+  const Walk w = walk_for(rows, cols, grid);
+#define CALL(R) hipLaunchKernelGGL(compress2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, d_in, w, static_cast<uint8_t*>(d_out))
   ZC2D_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
@@ -221,7 +292,9 @@ int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float*
   if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
   const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define CALL(R) hipLaunchKernelGGL(decompress2d_kernel<R>, dim3(grid_for(blocks)), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), rows, cols, d_out)
+  const unsigned grid = grid_for(blocks);
+  const Walk w = walk_for(rows, cols, grid);
+#define CALL(R) hipLaunchKernelGGL(decompress2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), w, d_out)
   ZC2D_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
