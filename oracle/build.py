@@ -1,4 +1,4 @@
-"""Compile the reference codecs (oracle/zc_ref.c, oracle/zc2d_ref.c) into oracle/libzc_ref.so.
+"""Compile the reference codecs (oracle/zc_ref.c, oracle/zc2d_ref.c, oracle/zl_ref.c) into oracle/libzc_ref.so.
 
 Test infrastructure: the product library never links or loads this.
 """
@@ -7,7 +7,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "zc_ref.c")
-SOURCES = [SRC, os.path.join(HERE, "zc2d_ref.c")]
+SOURCES = [SRC, os.path.join(HERE, "zc2d_ref.c"), os.path.join(HERE, "zl_ref.c")]
 LIB = os.path.join(HERE, "libzc_ref.so")
 
 # -fwrapv: 32-bit wrap-around is part of the format definition.
