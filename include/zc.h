@@ -48,7 +48,8 @@ enum {
   ZC_ERR_K = -5,        /* k outside [1, 16] */
   ZC_ERR_ALIGN = -6,    /* a device pointer is not 16-byte aligned */
   ZC_ERR_LAUNCH = -7,   /* the HIP runtime refused the launch */
-  ZC_ERR_DTYPE = -8     /* dtype is not ZC_BF16 or ZC_F16 */
+  ZC_ERR_DTYPE = -8,    /* dtype is not ZC_BF16 or ZC_F16 */
+  ZC_ERR_STREAM = -9    /* zl_stream_bytes: the buffer does not start with a complete lossless stream */
 };
 
 /* Element types of a message buffer.  The fp32 calls take no dtype argument. */
@@ -164,6 +165,42 @@ int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d
  * zc2d_compressed_size(rows,cols,rate) bytes and may contain arbitrary bytes.  d_out
  * must not overlap d_in. */
 int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream);
+
+/*
+ * Lossless messages, format "ZL-1": the role the paper's first hybrid scheme gives to a
+ * lossless codec of the MPC kind on model-parallel traffic (Sec. II-A, Sec. III-A and its
+ * table of collectives).  The message is n 32-bit words (fp32 values as bit patterns; any
+ * pattern, NaN and infinities included, comes back unchanged).  Chunks of 8192 words are
+ * coded on their own: a chunk is 256 groups of 32 words (word j of group g is chunk word
+ * 1024*(j/4) + 4*g + j%4); each word of a group becomes sign | (largest magnitude of the
+ * group - its magnitude), the 32 residuals are bit-transposed and the zero planes dropped.
+ * Stream: header (32 bytes: u32 magic "ZL01", u32 chunks, u64 n, u64 total bytes, u64 zero),
+ * a table of one u64 per chunk (binary 10 in the top two bits, below them the byte offset
+ * in the payload at which the chunk ends), then per chunk 256 references, 256 plane bitmaps
+ * and the non-zero planes.  The size of a stream depends on the data; it is at most
+ * zl_max_compressed_size(n) and is recorded in the header.  Device pointers, 16-byte
+ * aligned; the conventions at the top of this file apply.
+ */
+
+/* Capacity d_out must have for a message of n words: the size of the stream when no plane
+ * is dropped, 32 + ceil(n/8192) * (8 + 2048 + 32768).  0 if n exceeds 2^40. */
+size_t zl_max_compressed_size(size_t n);
+
+/* Compress d_in[0..n) (32-bit words) into a stream at d_out.  Bytes of d_out beyond the
+ * stream's own length are left as they were.  d_out must not overlap d_in.  Uses no memory
+ * besides d_in and d_out, and may be captured in a HIP graph. */
+int zl_compress(const void* d_in, size_t n, void* d_out, size_t out_cap, void* stream);
+
+/* Length in bytes of the stream at d_stream, read from its header into *h_bytes (a HOST
+ * pointer).  Waits for the work queued on `stream` before it returns.  ZC_ERR_STREAM if the
+ * buffer does not start with a complete stream. */
+int zl_stream_bytes(const void* d_stream, size_t* h_bytes, void* stream);
+
+/* Decompress the stream in d_in[0..in_bytes) into d_out[0..n).  n must be the message
+ * length the stream was made from, and in_bytes at least the stream's length; for anything
+ * else the output is unspecified, but no access leaves d_in[0..in_bytes) or d_out[0..n).
+ * ZC_ERR_CAPACITY if in_bytes cannot even hold the header and table for n words. */
+int zl_decompress(const void* d_in, size_t in_bytes, size_t n, void* d_out, void* stream);
 
 #ifdef __cplusplus
 }

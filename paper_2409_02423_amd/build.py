@@ -1,11 +1,11 @@
-"""Compile the HIP library (csrc/zc_kernels.hip, csrc/zc2d_kernels.hip) for gfx950 into
+"""Compile the HIP library (csrc/zc_kernels.hip, csrc/zc2d_kernels.hip, csrc/zl_kernels.hip) for gfx950 into
 libzc.so next to this file.  hipcc cross-compiles without a GPU."""
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = [os.path.join(HERE, "csrc", "zc_kernels.hip"), os.path.join(HERE, "csrc", "zc2d_kernels.hip")]
-DEPS = SOURCES + [os.path.join(HERE, "csrc", "zc_codec.h"), os.path.join(HERE, "csrc", "zc2d_codec.h"),
+SOURCES = [os.path.join(HERE, "csrc", f) for f in ("zc_kernels.hip", "zc2d_kernels.hip", "zl_kernels.hip")]
+DEPS = SOURCES + [os.path.join(HERE, "csrc", f) for f in ("zc_codec.h", "zc2d_codec.h", "zl_codec.h")] + [
                   os.path.join(HERE, "..", "include", "zc.h")]
 LIB = os.path.join(HERE, "libzc.so")
 

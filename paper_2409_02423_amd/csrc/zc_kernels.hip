@@ -529,6 +529,7 @@ const char* zc_strerror(int code) {
     case ZC_ERR_ALIGN: return "device pointer not 16-byte aligned";
     case ZC_ERR_LAUNCH: return "kernel launch failed";
     case ZC_ERR_DTYPE: return "dtype must be ZC_BF16 or ZC_F16";
+    case ZC_ERR_STREAM: return "not a complete lossless stream";
     default: return "unknown error code";
   }
 }

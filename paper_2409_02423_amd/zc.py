@@ -14,14 +14,15 @@ from . import build as _build
 
 ZC_OK = 0
 ZC_ERR_NULL, ZC_ERR_RATE, ZC_ERR_SIZE, ZC_ERR_CAPACITY = -1, -2, -3, -4
-ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH, ZC_ERR_DTYPE = -5, -6, -7, -8
+ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH, ZC_ERR_DTYPE, ZC_ERR_STREAM = -5, -6, -7, -8, -9
 ZC_F32, ZC_BF16, ZC_F16 = 0, 1, 2
 ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE = range(5)
 
 EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
            "zc_compress_half", "zc_decompress_half",
-           "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress")
+           "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress",
+           "zl_max_compressed_size", "zl_compress", "zl_stream_bytes", "zl_decompress")
 
 _lib = None
 
@@ -71,6 +72,11 @@ def lib():
                                     ctypes.c_size_t, ctypes.c_void_p]
         L.zc2d_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p]
+        L.zl_max_compressed_size.restype = ctypes.c_size_t
+        L.zl_max_compressed_size.argtypes = [ctypes.c_size_t]
+        L.zl_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.zl_stream_bytes.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t), ctypes.c_void_p]
+        L.zl_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -309,4 +315,53 @@ def zc2d_decompress(d_in, rows, cols, rate, d_out=None, stream=None):
                                _stream_handle(stream))
     if rc != ZC_OK:
         raise ZcError(rc, "zc2d_decompress")
+    return d_out
+
+
+def zl_max_compressed_size(n):
+    return int(lib().zl_max_compressed_size(int(n)))
+
+
+def _check_words(t, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.element_size() == 4 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of 32-bit items" % what)
+
+
+def zl_compress(d_in, d_out=None, stream=None):
+    """CUDA tensor of 32-bit items -> uint8 CUDA tensor of zl_max_compressed_size(n) bytes that
+    starts with the lossless stream; zl_stream_bytes gives the stream's own length."""
+    _check_words(d_in, "d_in")
+    n = d_in.numel()
+    if d_out is None:
+        d_out = torch.empty(zl_max_compressed_size(n), dtype=torch.uint8, device=d_in.device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zl_compress(d_in.data_ptr(), n, d_out.data_ptr(), d_out.numel(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zl_compress")
+    return d_out
+
+
+def zl_stream_bytes(d_stream, stream=None):
+    """Length of the lossless stream at the start of d_stream (waits for the stream's work)."""
+    _check_device_tensor(d_stream, torch.uint8, "d_stream")
+    if d_stream.numel() < 32:
+        raise ValueError("d_stream is shorter than a header")
+    size = ctypes.c_size_t(0)
+    rc = lib().zl_stream_bytes(d_stream.data_ptr(), ctypes.byref(size), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zl_stream_bytes")
+    return int(size.value)
+
+
+def zl_decompress(d_in, n, d_out=None, dtype=torch.float32, stream=None):
+    """Lossless stream (uint8 CUDA tensor, at least the stream's length) -> n 32-bit items."""
+    _check_device_tensor(d_in, torch.uint8, "d_in")
+    if d_out is None:
+        d_out = torch.empty(int(n), dtype=dtype, device=d_in.device)
+    _check_words(d_out, "d_out")
+    if d_out.numel() < n:
+        raise ValueError("d_out holds %d items, need %d" % (d_out.numel(), n))
+    rc = lib().zl_decompress(d_in.data_ptr(), d_in.numel(), int(n), d_out.data_ptr(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zl_decompress")
     return d_out

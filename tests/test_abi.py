@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "zc.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(zc(?:2d)?_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(z(?:c|c2d|l)_[a-z_]+)\s*\(", text))
     assert declared == set(zc.EXPORTS)
     L = ctypes.CDLL(zc.library_path()) if os.path.exists(zc.library_path()) else zc.lib()
     for name in declared:
@@ -41,11 +41,11 @@ def test_sizes_and_policy():
 
 def test_error_strings():
     seen = set()
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         s = zc.zc_strerror(code)
         assert s and s != "unknown error code"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert zc.zc_strerror(-99) == "unknown error code"
 
 
@@ -126,3 +126,27 @@ def test_2d_sizes_and_argument_errors():
     assert L.zc2d_decompress(None, 4, 4, 4, good, None) == zc.ZC_ERR_NULL
     assert L.zc2d_decompress(good, 4, 4, 4, odd, None) == zc.ZC_ERR_ALIGN
     assert L.zc2d_decompress(good, 1 << 41, 1, 4, good, None) == zc.ZC_ERR_SIZE
+
+
+def test_lossless_sizes_and_argument_errors():
+    assert zc.zl_max_compressed_size(0) == 32
+    assert zc.zl_max_compressed_size(1) == 32 + 8 + 2048 + 32768
+    assert zc.zl_max_compressed_size(8192) == 32 + 8 + 2048 + 32768
+    assert zc.zl_max_compressed_size(8193) == 32 + 2 * (8 + 2048 + 32768)
+    assert zc.zl_max_compressed_size(1 << 28) == 32 + (1 << 15) * (8 + 2048 + 32768)
+    assert zc.zl_max_compressed_size((1 << 40) + 1) == 0
+    L = zc.lib()
+    good, odd = 0x10000, 0x10004  # never dereferenced: every call fails validation first
+    cap = zc.zl_max_compressed_size(100)
+    assert L.zl_compress(good, 100, None, cap, None) == zc.ZC_ERR_NULL
+    assert L.zl_compress(None, 100, good, cap, None) == zc.ZC_ERR_NULL
+    assert L.zl_compress(odd, 100, good, cap, None) == zc.ZC_ERR_ALIGN
+    assert L.zl_compress(good, 100, odd, cap, None) == zc.ZC_ERR_ALIGN
+    assert L.zl_compress(good, 100, good, cap - 1, None) == zc.ZC_ERR_CAPACITY
+    assert L.zl_compress(good, (1 << 40) + 1, good, 1 << 62, None) == zc.ZC_ERR_SIZE
+    assert L.zl_decompress(None, 64, 100, good, None) == zc.ZC_ERR_NULL
+    assert L.zl_decompress(good, 64, 100, None, None) == zc.ZC_ERR_NULL
+    assert L.zl_decompress(good, 39, 100, good, None) == zc.ZC_ERR_CAPACITY      # header + one table entry = 40 bytes
+    assert L.zl_decompress(good, 64, 100, odd, None) == zc.ZC_ERR_ALIGN
+    assert L.zl_decompress(good, 32, 0, None, None) == zc.ZC_OK                  # empty message: nothing to write
+    assert L.zl_stream_bytes(None, None, None) == zc.ZC_ERR_NULL
