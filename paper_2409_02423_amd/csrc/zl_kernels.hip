@@ -2,9 +2,11 @@
 //
 // One workgroup of 256 lanes per chunk of 8192 words; a lane owns one group of 32 words
 // (its eight 16-byte reads), so residuals, the bit transpose and the test for empty
-// planes all stay in registers.  The non-zero planes are compacted through LDS (a
-// workgroup-wide prefix sum of the per-lane counts gives every lane its place) and
-// leave as one contiguous span per chunk.
+// planes all stay in registers.  A workgroup-wide prefix sum of the per-lane plane counts
+// gives every lane its place in the chunk; each wavefront then moves its planes between
+// registers and its contiguous span of the stream through 4 KiB of LDS of its own, half
+// of its lanes at a time, with no further barrier (16 KiB of LDS per workgroup, so that
+// seven workgroups fit on a CU and hide each other's waits).
 //
 // Chunks have data-dependent sizes, so a chunk's place in the stream is the sum of the
 // sizes before it.  That sum is formed in the same launch: chunk numbers are handed out
@@ -26,6 +28,12 @@ namespace {
 
 constexpr int kThreads = zl::kGroups;
 constexpr uint32_t kSpinLimit = 1u << 22;
+constexpr int kWaveStageWords = 32 * 33;   // planes of 32 lanes: a wavefront's LDS, one spare word per 32
+
+// Where plane word i of a half-wavefront sits in its LDS.  Lanes reach their planes with a
+// stride of their plane count (32 if nothing is dropped): the spare word per 32 keeps such
+// strides off a single bank, and consecutive words stay consecutive for the copy.
+__device__ __forceinline__ uint32_t staged(uint32_t i) { return i + (i >> 5); }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -73,25 +81,45 @@ __device__ __forceinline__ uint64_t wave_sum64(uint64_t v) {
   return v;
 }
 
-// Exclusive prefix sum of `count` over the 256 lanes of the workgroup; `total` gets the sum.
-__device__ __forceinline__ uint32_t workgroup_exclusive_sum(uint32_t count, uint32_t* wave_totals, uint32_t& total) {
+// Places of the planes within a chunk, from the per-lane counts.
+struct Places {
+  uint32_t in_wave;      // planes of lower lanes of the same wavefront
+  uint32_t wave_total;   // planes of the whole wavefront
+  uint32_t wave_start;   // planes of lower wavefronts
+  uint32_t total;        // planes of the chunk
+};
+
+__device__ __forceinline__ Places workgroup_places(uint32_t count, uint32_t* wave_totals) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t incl = wave_inclusive_sum(count, lane);
   if (lane == 63) wave_totals[wave] = incl;
   __syncthreads();
-  uint32_t before = 0, all = 0;
+  Places p;
+  p.in_wave = incl - count;
+  p.wave_total = wave_totals[wave];
+  p.wave_start = 0;
+  p.total = 0;
 #pragma unroll
   for (int w = 0; w < kThreads / 64; ++w) {
     const uint32_t t = wave_totals[w];
-    before += w < wave ? t : 0u;
-    all += t;
+    p.wave_start += w < wave ? t : 0u;
+    p.total += t;
   }
-  total = all;
-  return before + incl - count;
+  return p;
 }
 
-// Sum of the sizes of chunks 0..c-1, read from the table (run by one whole wavefront).
-// Returns false if an entry stayed empty for kSpinLimit polls.
+// Span, within the wavefront's planes, of the half of its lanes that starts at lane 32*half.
+__device__ __forceinline__ void half_span(const Places& p, int half, uint32_t& start, uint32_t& end) {
+  const uint32_t middle = (uint32_t)__shfl((int)p.in_wave, 32);
+  start = half ? middle : 0u;
+  end = half ? p.wave_total : middle;
+}
+
+// Sum of the sizes of chunks 0..c-1, read from the table (run by one whole wavefront):
+// 64 entries per pass, the lane's being the chunk at distance lane + 1 before c.  (Wider
+// passes were slower: the polls of all workgroups in flight fall on the same few hundred
+// table entries, and it is the number of these loads that costs.)  Returns false if a
+// needed entry stayed empty for kSpinLimit polls.
 __device__ bool bytes_before(uint64_t* table, uint32_t c, int lane, uint64_t& before) {
   uint64_t sum = 0;
   int64_t base = (int64_t)c - 1;
@@ -120,7 +148,7 @@ __device__ bool bytes_before(uint64_t* table, uint32_t c, int lane, uint64_t& be
 
 __global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* __restrict__ in, size_t n, uint8_t* out,
                                                                uint32_t chunks) {
-  __shared__ uint32_t stage[zl::kChunkWords];
+  __shared__ uint32_t stage[kWaveStageWords * (kThreads / 64)];
   __shared__ uint32_t wave_totals[kThreads / 64];
   __shared__ uint32_t my_chunk;
   __shared__ uint64_t my_start;
@@ -156,13 +184,8 @@ __global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* _
   }
   uint32_t reference;
   const uint32_t bitmap = zl::to_planes(w, reference);
-  const uint32_t count = (uint32_t)__builtin_popcount(bitmap);
-  uint32_t total_words;
-  uint32_t pos = workgroup_exclusive_sum(count, wave_totals, total_words);
-#pragma unroll
-  for (int k = 0; k < 32; ++k)
-    if ((bitmap >> k) & 1u) stage[pos++] = w[k];
-  const uint64_t bytes = zl::kFixedChunkBytes + 4ull * total_words;
+  const Places at = workgroup_places((uint32_t)__builtin_popcount(bitmap), wave_totals);
+  const uint64_t bytes = zl::kFixedChunkBytes + 4ull * at.total;
 
   if (wave == 0) {
     if (lane == 0)
@@ -192,14 +215,30 @@ __global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* _
   uint32_t* dst = reinterpret_cast<uint32_t*>(payload + my_start);
   dst[tid] = reference;
   dst[kThreads + tid] = bitmap;
-  dst += 2 * kThreads;
-  for (uint32_t i = tid; i < total_words; i += kThreads) dst[i] = stage[i];
+  dst += 2 * kThreads + at.wave_start;
+  // the wavefront's planes, 32 lanes at a time: into its LDS by lane, out of it by address
+  // (LDS operations of one wavefront take effect in program order)
+  uint32_t* mine = stage + kWaveStageWords * wave;
+#pragma unroll 1
+  for (int half = 0; half < 2; ++half) {
+    uint32_t start, end;
+    half_span(at, half, start, end);
+    if ((lane >> 5) == half) {
+      uint32_t pos = at.in_wave - start;
+#pragma unroll
+      for (int k = 0; k < 32; ++k)
+        if ((bitmap >> k) & 1u) mine[staged(pos++)] = w[k];
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t i = lane; i < end - start; i += 64) dst[start + i] = mine[staged(i)];
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 // in_bytes: size of the buffer that holds the stream; every read stays below it.
 __global__ __launch_bounds__(kThreads) void zl_decompress_kernel(const uint8_t* __restrict__ in, size_t in_bytes, size_t n,
                                                                  uint32_t* __restrict__ out, uint32_t chunks) {
-  __shared__ uint32_t stage[zl::kChunkWords + 64];   // a lane may look one past its last plane
+  __shared__ uint32_t stage[zl::kChunkWords + zl::kChunkWords / 32 + 64];   // spare words as in staged(); a lane may look one past its last plane
   __shared__ uint32_t wave_totals[kThreads / 64];
   const uint64_t* table = reinterpret_cast<const uint64_t*>(in + zl::kHeaderBytes);
   const uint64_t room = in_bytes - zl::kHeaderBytes - 8 * (uint64_t)chunks;   // the host checked that this is not negative
@@ -216,17 +255,26 @@ __global__ __launch_bounds__(kThreads) void zl_decompress_kernel(const uint8_t* 
 
   const uint32_t reference = (uint64_t)tid < words ? src[tid] : 0u;
   const uint32_t bitmap = (uint64_t)(kThreads + tid) < words ? src[kThreads + tid] : 0u;
-  uint32_t total_words;
-  uint32_t pos = workgroup_exclusive_sum((uint32_t)__builtin_popcount(bitmap), wave_totals, total_words);
-  const uint64_t stored = words > 2 * kThreads ? words - 2 * kThreads : 0;
-  for (uint32_t i = tid; i < total_words; i += kThreads) stage[i] = i < stored ? src[2 * kThreads + i] : 0u;
-  __syncthreads();
-
+  // the chunk's plane words, as many as the span really holds: fetched by address before
+  // anything is known about them, 32 loads in flight per lane
+  const uint64_t held = words > 2 * kThreads ? words - 2 * kThreads : 0;
+  const uint32_t stored = held < (uint64_t)zl::kChunkWords ? (uint32_t)held : (uint32_t)zl::kChunkWords;
+  src += 2 * kThreads;
   uint32_t p[32];
+#pragma unroll
+  for (int q = 0; q < 32; ++q) {
+    const uint32_t i = tid + kThreads * q;
+    p[q] = i < stored ? src[i] : 0u;
+  }
+  const Places at = workgroup_places((uint32_t)__builtin_popcount(bitmap), wave_totals);
+#pragma unroll
+  for (int q = 0; q < 32; ++q) stage[staged(tid + kThreads * q)] = p[q];
+  __syncthreads();
+  uint32_t pos = at.wave_start + at.in_wave;
 #pragma unroll
   for (int k = 0; k < 32; ++k) {
     const bool present = (bitmap >> k) & 1u;
-    p[k] = present ? stage[pos] : 0u;
+    p[k] = present ? stage[staged(pos)] : 0u;
     pos += present ? 1u : 0u;
   }
   zl::from_planes(p, reference);
