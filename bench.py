@@ -249,6 +249,33 @@ def main():
             "relative_rms_error": round(rel2, 5), "relative_rms_error_blocks_of_4": round(rel1, 5)}
     del xm, ym
 
+    # the lossless codec on the same buffer, as fp32 and as bf16 content widened to fp32 (not part of `value`)
+    lossless = {}
+    cl = torch.empty(zc.zl_max_compressed_size(n), dtype=torch.uint8, device=dev)
+    for label, xl in (("fp32", x), ("bf16_content", x.to(torch.bfloat16).to(torch.float32))):
+        zc.zl_compress(xl, d_out=cl)
+        size = zc.zl_stream_bytes(cl)
+        ml = []
+        for _ in range(12):
+            e = [ev() for _ in range(3)]
+            e[0].record()
+            zc.zl_compress(xl, d_out=cl)
+            e[1].record()
+            zc.zl_decompress(cl[:size], n, d_out=y)
+            e[2].record()
+            ml.append(e)
+        torch.cuda.synchronize()
+        tc = float(np.median([m[0].elapsed_time(m[1]) for m in ml[2:]]))
+        td = float(np.median([m[1].elapsed_time(m[2]) for m in ml[2:]]))
+        moved = 4 * n + size
+        lossless[label] = {"stream_over_message": round(size / (4.0 * n), 4),
+                           "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+                           "compress_hbm_frac": round(moved / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                           "decompress_hbm_frac": round(moved / (td * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                           "exact": bool(torch.equal(y.view(torch.int32), xl.view(torch.int32)))}
+        del xl
+    del cl
+
     # error of the lossy round trip against the original input (reported, not a target)
     back = zc.zc_decompress(c, n, rate)
     err = (back - x).double()
@@ -264,7 +291,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
                                "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
-        "kernels": kernels, "ring_hop": ring_hop, "half_precision": half_precision, "blocks_4x4": blocks_4x4, "roofline": roofline, "round_trip_error": quality,
+        "kernels": kernels, "ring_hop": ring_hop, "half_precision": half_precision, "blocks_4x4": blocks_4x4, "lossless": lossless, "roofline": roofline, "round_trip_error": quality,
     }
 
     if args.sweep:
