@@ -9,17 +9,26 @@
 // seven workgroups fit on a CU and hide each other's waits).
 //
 // Chunks have data-dependent sizes, so a chunk's place in the stream is the sum of the
-// sizes before it.  That sum is formed in the same launch: chunk numbers are handed out
-// by a counter in the order in which workgroups start, a workgroup publishes its own
-// size in the stream's table as soon as it knows it, then adds up its predecessors'
-// entries, 64 at a time, back to the nearest one that already holds a running total,
-// and replaces its entry by its own running total.  Every entry a workgroup waits for
-// belongs to a workgroup that has started and that publishes before it waits, so every
-// wait ends; a spin limit turns the impossible case into an error mark in the header.
-// The table is part of the stream (the decoder needs it) and the counter ends up as the
-// header's chunk count: no memory beyond input and output is used.
+// sizes before it.  That sum is formed in the same launch.  The compress kernel runs about
+// as many workgroups as fit on the chip at once; each takes chunk numbers from a counter,
+// one after the other, and publishes a chunk's own size in the stream's table as soon as
+// the chunk is coded.  The coded chunk then waits in registers while the workgroup codes
+// its next one; only after that does the workgroup add up the entries of the chunks before
+// the waiting one, 64 at a time, back to the nearest entry that already holds a running
+// total, replace the chunk's entry by its own running total and write the chunk.  By then
+// most of what the sum needs has arrived, so the look-back rarely has to poll.
+// Every entry a workgroup waits for belongs to a chunk number taken by a running workgroup,
+// and between taking a number and publishing that chunk's size a workgroup waits for no
+// other workgroup; so every wait ends (also with several such kernels running at once,
+// which a fixed assignment of chunks to workgroups would not survive).  A spin limit turns
+// the impossible case into a flaw mark in the header.  The counter is the header's chunk
+// count; it runs past its end (every workgroup asks once too often) and a last one-lane
+// kernel sets it, and the rest of the header, to their final values.  The table is part
+// of the stream (the decoder needs it): no memory beyond input and output is used.
+// What bounds the kernel from below is the counter itself: about 13 ns per chunk number.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/zc.h"
 #include "zl_codec.h"
@@ -146,29 +155,10 @@ __device__ bool bytes_before(uint64_t* table, uint32_t c, int lane, uint64_t& be
   return true;
 }
 
-__global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* __restrict__ in, size_t n, uint8_t* out,
-                                                               uint32_t chunks) {
-  __shared__ uint32_t stage[kWaveStageWords * (kThreads / 64)];
-  __shared__ uint32_t wave_totals[kThreads / 64];
-  __shared__ uint32_t my_chunk;
-  __shared__ uint64_t my_start;
-  __shared__ uint32_t failed;
-  Header* header = reinterpret_cast<Header*>(out);
-  uint64_t* table = reinterpret_cast<uint64_t*>(out + zl::kHeaderBytes);
-  uint8_t* payload = out + zl::kHeaderBytes + 8 * (size_t)chunks;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-  if (tid == 0) {
-    my_chunk = __hip_atomic_fetch_add(&header->chunks, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    failed = 0;
-  }
-  __syncthreads();
-  const uint32_t c = my_chunk;
-  if (c >= chunks) return;   // cannot happen with one workgroup per chunk; keeps every access in bounds regardless
-
-  // the lane's group: words 1024*t + 4*tid .. +3 of the chunk, t = 0..7
+// The lane's group of chunk c: words 1024*t + 4*tid .. +3 of the chunk, t = 0..7; words
+// past the end of the message read as zero.
+__device__ __forceinline__ void load_group(const uint32_t* __restrict__ in, size_t n, uint32_t c, int tid, uint32_t (&w)[32]) {
   const size_t base = (size_t)c * zl::kChunkWords;
-  uint32_t w[32];
   if (base + zl::kChunkWords <= n) {
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
@@ -182,57 +172,116 @@ __global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* _
       w[j] = i < n ? in[i] : 0u;
     }
   }
-  uint32_t reference;
-  const uint32_t bitmap = zl::to_planes(w, reference);
-  const Places at = workgroup_places((uint32_t)__builtin_popcount(bitmap), wave_totals);
-  const uint64_t bytes = zl::kFixedChunkBytes + 4ull * at.total;
+}
 
-  if (wave == 0) {
-    if (lane == 0)
-      __hip_atomic_store(&table[c], (c == 0 ? zl::kEnd : zl::kOwnSize) | bytes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    uint64_t before = 0;
-    const bool ok = c == 0 || bytes_before(table, c, lane, before);
-    if (lane == 0) {
-      if (!ok) {
-        failed = 1;
-        __hip_atomic_fetch_or(&header->flaw, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      // publish a running total in any case, so that no later chunk waits for this one
-      if (c != 0)
-        __hip_atomic_store(&table[c], zl::kEnd | (before + bytes), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      my_start = before;
-      if (c == chunks - 1 && ok) {   // the last chunk completes the header
-        __hip_atomic_store(&header->magic, zl::kMagic, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&header->n, (uint64_t)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&header->total, zl::kHeaderBytes + 8ull * chunks + before + bytes, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
+// A coded chunk that waits, in registers, for its place in the stream.
+struct Coded {
+  uint32_t planes[32];
+  uint32_t reference, bitmap, chunk;
+  Places at;
+};
+
+__global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* __restrict__ in, size_t n, uint8_t* out,
+                                                               uint32_t chunks) {
+  __shared__ uint32_t stage[kWaveStageWords * (kThreads / 64)];
+  __shared__ uint32_t wave_totals[kThreads / 64];
+  __shared__ uint32_t next_chunk;
+  __shared__ uint64_t my_start;
+  __shared__ uint32_t failed;
+  Header* header = reinterpret_cast<Header*>(out);
+  uint64_t* table = reinterpret_cast<uint64_t*>(out + zl::kHeaderBytes);
+  uint8_t* payload = out + zl::kHeaderBytes + 8 * (size_t)chunks;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  if (tid == 0) {
+    next_chunk = __hip_atomic_fetch_add(&header->chunks, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    failed = 0;
   }
   __syncthreads();
-  if (failed) return;   // the stream is marked flawed; nothing of this chunk is written
+  uint32_t c = next_chunk;
+  if (c >= chunks) return;
 
-  uint32_t* dst = reinterpret_cast<uint32_t*>(payload + my_start);
-  dst[tid] = reference;
-  dst[kThreads + tid] = bitmap;
-  dst += 2 * kThreads + at.wave_start;
-  // the wavefront's planes, 32 lanes at a time: into its LDS by lane, out of it by address
-  // (LDS operations of one wavefront take effect in program order)
-  uint32_t* mine = stage + kWaveStageWords * wave;
-#pragma unroll 1
-  for (int half = 0; half < 2; ++half) {
-    uint32_t start, end;
-    half_span(at, half, start, end);
-    if ((lane >> 5) == half) {
-      uint32_t pos = at.in_wave - start;
-#pragma unroll
-      for (int k = 0; k < 32; ++k)
-        if ((bitmap >> k) & 1u) mine[staged(pos++)] = w[k];
+  // A workgroup codes chunk after chunk.  A chunk's size is published as soon as it is
+  // coded; its place is worked out, and it is written, only after the next chunk has
+  // been coded in turn, by which time most of what its place depends on has arrived.
+  // No wait for another workgroup lies between taking a chunk number and publishing
+  // that chunk's size.
+  Coded held;
+  bool holding = false;
+  for (;;) {
+    const bool coding = c < chunks;
+    Coded now;
+    if (coding) {
+      load_group(in, n, c, tid, now.planes);
+      now.bitmap = zl::to_planes(now.planes, now.reference);
+      now.chunk = c;
+      now.at = workgroup_places((uint32_t)__builtin_popcount(now.bitmap), wave_totals);
+      if (tid == 0)
+        __hip_atomic_store(&table[c], (c == 0 ? zl::kEnd : zl::kOwnSize) | (zl::kFixedChunkBytes + 4ull * now.at.total),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __builtin_amdgcn_wave_barrier();
-    for (uint32_t i = lane; i < end - start; i += 64) dst[start + i] = mine[staged(i)];
-    __builtin_amdgcn_wave_barrier();
+    if (holding) {
+      const uint64_t bytes = zl::kFixedChunkBytes + 4ull * held.at.total;
+      if (wave == 0) {
+        uint64_t before = 0;
+        const bool ok = held.chunk == 0 || bytes_before(table, held.chunk, lane, before);
+        if (lane == 0) {
+          if (!ok) {
+            failed = 1;
+            __hip_atomic_fetch_or(&header->flaw, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+          // publish a running total in any case, so that no later chunk waits for this one
+          if (held.chunk != 0)
+            __hip_atomic_store(&table[held.chunk], zl::kEnd | (before + bytes), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          my_start = before;
+        }
+      }
+      __syncthreads();
+    }
+    // the next chunk number travels while the held chunk is written
+    uint32_t asked = 0;
+    if (coding && tid == 0) asked = __hip_atomic_fetch_add(&header->chunks, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (holding && !failed) {   // (a flawed stream is marked in the header; nothing more of it is written)
+      uint32_t* dst = reinterpret_cast<uint32_t*>(payload + my_start);
+      dst[tid] = held.reference;
+      dst[kThreads + tid] = held.bitmap;
+      dst += 2 * kThreads + held.at.wave_start;
+      // the wavefront's planes, 32 lanes at a time: into its LDS by lane, out of it by address
+      // (LDS operations of one wavefront take effect in program order)
+      uint32_t* mine = stage + kWaveStageWords * wave;
+#pragma unroll 1
+      for (int half = 0; half < 2; ++half) {
+        uint32_t start, end;
+        half_span(held.at, half, start, end);
+        if ((lane >> 5) == half) {
+          uint32_t pos = held.at.in_wave - start;
+#pragma unroll
+          for (int k = 0; k < 32; ++k)
+            if ((held.bitmap >> k) & 1u) mine[staged(pos++)] = held.planes[k];
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (uint32_t i = lane; i < end - start; i += 64) dst[start + i] = mine[staged(i)];
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+    if (!coding) break;
+    if (tid == 0) next_chunk = asked;
+    held = now;
+    holding = true;
+    __syncthreads();
+    c = next_chunk;
   }
+}
+
+// Completes the header once every chunk is placed (the chunk counter has run past its end).
+__global__ void zl_finish_kernel(uint8_t* out, size_t n, uint32_t chunks) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  Header* header = reinterpret_cast<Header*>(out);
+  const uint64_t* table = reinterpret_cast<const uint64_t*>(out + zl::kHeaderBytes);
+  header->chunks = chunks;
+  header->n = n;
+  header->total = zl::kHeaderBytes + 8ull * chunks + (table[chunks - 1] & zl::kValueMask);
+  header->magic = zl::kMagic;
 }
 
 // in_bytes: size of the buffer that holds the stream; every read stays below it.
@@ -295,6 +344,26 @@ __global__ __launch_bounds__(kThreads) void zl_decompress_kernel(const uint8_t* 
   }
 }
 
+int compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+  return cus;
+}
+
+// Workgroups of the compress kernel per CU; ZL_WORKGROUPS_PER_CU overrides it for tuning runs.
+int workgroups_per_cu() {
+  static int forced = -1;
+  if (forced < 0) {
+    forced = 0;
+    if (const char* e = getenv("ZL_WORKGROUPS_PER_CU")) {
+      const int v = atoi(e);
+      if (v >= 1 && v <= 64) forced = v;
+    }
+  }
+  return forced > 0 ? forced : 4;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 constexpr size_t kMaxWords = (size_t)1 << 40;
 
@@ -326,8 +395,12 @@ int zl_compress(const void* d_in, size_t n, void* d_out, size_t out_cap, void* s
   const unsigned zgrid = (unsigned)((clear + 255) / 256 < 1024 ? (clear + 255) / 256 : 1024);
   hipLaunchKernelGGL(zero_words_kernel, dim3(zgrid), dim3(256), 0, s, static_cast<uint64_t*>(d_out), clear);
   if (hipGetLastError() != hipSuccess) return ZC_ERR_LAUNCH;
-  hipLaunchKernelGGL(zl_compress_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, static_cast<const uint32_t*>(d_in), n,
+  const size_t resident = (size_t)compute_units() * workgroups_per_cu();
+  const unsigned grid = (unsigned)(chunks < resident ? chunks : resident);
+  hipLaunchKernelGGL(zl_compress_kernel, dim3(grid), dim3(kThreads), 0, s, static_cast<const uint32_t*>(d_in), n,
                      static_cast<uint8_t*>(d_out), (uint32_t)chunks);
+  if (hipGetLastError() != hipSuccess) return ZC_ERR_LAUNCH;
+  hipLaunchKernelGGL(zl_finish_kernel, dim3(1), dim3(64), 0, s, static_cast<uint8_t*>(d_out), n, (uint32_t)chunks);
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
 }
 
