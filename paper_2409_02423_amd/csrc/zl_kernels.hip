@@ -128,8 +128,9 @@ __device__ __forceinline__ void half_span(const Places& p, int half, uint32_t& s
 // 64 entries per pass, the lane's being the chunk at distance lane + 1 before c.  (Wider
 // passes were slower: the polls of all workgroups in flight fall on the same few hundred
 // table entries, and it is the number of these loads that costs.)  Returns false if a
-// needed entry stayed empty for kSpinLimit polls.
-__device__ bool bytes_before(uint64_t* table, uint32_t c, int lane, uint64_t& before) {
+// needed entry stayed empty for kSpinLimit polls, or if the stream has been marked flawed
+// meanwhile (after one such failure nobody waits any more, so the launch ends at once).
+__device__ bool bytes_before(uint64_t* table, const uint64_t* flaw, uint32_t c, int lane, uint64_t& before) {
   uint64_t sum = 0;
   int64_t base = (int64_t)c - 1;
   while (base >= 0) {
@@ -145,6 +146,7 @@ __device__ bool bytes_before(uint64_t* table, uint32_t c, int lane, uint64_t& be
       const uint64_t needed = first >= 63u ? ~0ull : ((2ull << first) - 1ull);
       if ((empty & needed) == 0) break;
       if (++polls > kSpinLimit) return false;
+      if ((polls & 255u) == 0u && __hip_atomic_load(flaw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return false;
       __builtin_amdgcn_s_sleep(2);
     }
     sum += wave_sum64((uint32_t)lane <= first ? (s & zl::kValueMask) : 0ull);
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* _
       const uint64_t bytes = zl::kFixedChunkBytes + 4ull * held.at.total;
       if (wave == 0) {
         uint64_t before = 0;
-        const bool ok = held.chunk == 0 || bytes_before(table, held.chunk, lane, before);
+        const bool ok = held.chunk == 0 || bytes_before(table, &header->flaw, held.chunk, lane, before);
         if (lane == 0) {
           if (!ok) {
             failed = 1;

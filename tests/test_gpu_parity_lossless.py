@@ -128,6 +128,28 @@ def test_errors_and_side_stream(gpu, ref):
     _same(_host(y).view(np.uint32), _host(x).view(np.uint32), "side stream round trip")
 
 
+def test_two_compressions_at_once(gpu, ref):
+    """Two messages compressed on two streams at the same time (each kernel alone would fill
+    the chip): both streams must come out as the reference's, several times over."""
+    import torch
+    a = workloads.gradient_iid(600 * C + 11, config=1, index=8)
+    b = workloads.activation_gelu(500 * C + 7, config=3, index=8)
+    want_a, want_b = ref.compress(a), ref.compress(b)
+    da, db = _dev(a), _dev(b)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(5):
+        print("two compressions at once, repetition", rep, flush=True)
+        with torch.cuda.stream(s1):
+            ca = gpu.zl_compress(da, stream=s1)
+        with torch.cuda.stream(s2):
+            cb = gpu.zl_compress(db, stream=s2)
+        s1.synchronize()
+        s2.synchronize()
+        _same(_host(ca[:gpu.zl_stream_bytes(ca)]), want_a, "stream a, repetition %d" % rep)
+        _same(_host(cb[:gpu.zl_stream_bytes(cb)]), want_b, "stream b, repetition %d" % rep)
+
+
 def test_arbitrary_bytes_stay_in_bounds(gpu):
     """Streams that no encoder produced: the output is unspecified, but nothing outside the
     output buffer is written and the call returns."""
