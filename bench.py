@@ -104,6 +104,9 @@ def main():
     ap.add_argument("--rates", type=int, nargs="+", default=None,
                     help="instead of the benchmark line: time the same three-call step at these rates on 2^28 values "
                          "(gradient bucket below rate 16, GELU activations from rate 16 up); one JSON list on stdout")
+    ap.add_argument("--lossless", action="store_true",
+                    help="instead of the benchmark line: time zl_compress / zl_decompress alone on the 2^28-word gradient "
+                         "bucket (fp32), 12 pairs of launches; one JSON object on stdout")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -118,6 +121,9 @@ def main():
 
     if args.rates:
         print(json.dumps(rate_loop(torch, zc, workloads, dev, args.rates)))
+        return
+    if args.lossless:
+        print(json.dumps(lossless_loop(torch, zc, workloads, dev, calibrate=args.calibrate_copy)))
         return
 
     cfg = workloads.CONFIGS[2]
@@ -307,6 +313,28 @@ def main():
         threads = min(16, len(os.sched_getaffinity(0)))
         result["cpu_baseline"] = cpu_baseline(x_host, rate, 1 << args.cpu_sample_log2, threads)
     print(json.dumps(result))
+
+
+def lossless_loop(torch, zc, workloads, dev, reps=12, calibrate=False):
+    x = torch.from_numpy(workloads.config_buffers(2)[0][1]).to(dev)
+    n = x.numel()
+    c = torch.empty(zc.zl_max_compressed_size(n), dtype=torch.uint8, device=dev)
+    y = torch.empty_like(x)
+    zc.zl_compress(x, d_out=c)
+    size = zc.zl_stream_bytes(c)
+    tc = time_events(lambda: zc.zl_compress(x, d_out=c), reps, torch)
+    td = time_events(lambda: zc.zl_decompress(c[:size], n, d_out=y), reps, torch)
+    if calibrate:
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+    moved = 4 * n + size
+    mc, md = float(np.median(tc[2:])), float(np.median(td[2:]))
+    return {"workload": "configs[1] gradient bucket, 2^28 words", "stream_bytes": size, "stream_over_message": round(size / (4.0 * n), 4),
+            "compress_ms": round(mc, 4), "decompress_ms": round(md, 4),
+            "compress_hbm_frac": round(moved / (mc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "decompress_hbm_frac": round(moved / (md * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "exact": bool(torch.equal(y.view(torch.int32), x.view(torch.int32)))}
 
 
 def rate_loop(torch, zc, workloads, dev, rates, reps=12):
