@@ -48,7 +48,7 @@ void zc_ref_inv_lift(int32_t v[4]);
 uint32_t zc_ref_negabinary(int32_t c);
 int32_t zc_ref_inv_negabinary(uint32_t u);
 
-enum { ZC2D_OK = 0, ZC2D_ERR_NULL = -1, ZC2D_ERR_RATE = -2, ZC2D_ERR_CAPACITY = -4 };
+enum { ZC2D_OK = 0, ZC2D_ERR_NULL = -1, ZC2D_ERR_RATE = -2, ZC2D_ERR_CAPACITY = -4, ZC2D_ERR_K = -5 };
 
 int zc2d_ref_rate_supported(int rate) { return rate >= 1 && rate <= 32; }
 
@@ -236,6 +236,43 @@ int zc2d_ref_decompress(const void *in, size_t rows, size_t cols, int rate, floa
           size_t rr = 4 * bi + (size_t)r, cc = 4 * bj + (size_t)c;
           if (rr < rows && cc < cols) out[rr * cols + cc] = x[4 * r + c];
         }
+    }
+  return ZC2D_OK;
+}
+
+/* The reduce-scatter step of the compressed all-reduce (Sec. IV-A) on matrix-shaped
+ * messages: decode the k incoming matrices block by block, add them element by element
+ * in fp32 in index order ((d0 + d1) + d2) + ..., and encode the sum.  The result is
+ * compress(sum): where a block sticks out of the matrix it is filled with the last valid
+ * row / column of the sum, not with the sum of the inputs' fills.  `out` may be the
+ * same buffer as in[0]. */
+int zc2d_ref_reduce_compressed(const void *const *in, int k, size_t rows, size_t cols, int rate,
+                               void *out, size_t out_cap) {
+  if (!zc2d_ref_rate_supported(rate)) return ZC2D_ERR_RATE;
+  if (k < 1 || k > 16) return ZC2D_ERR_K;
+  if (rows == 0 || cols == 0) return ZC2D_OK;
+  if (!in || !out) return ZC2D_ERR_NULL;
+  for (int c = 0; c < k; ++c)
+    if (!in[c]) return ZC2D_ERR_NULL;
+  if (out_cap < zc2d_ref_compressed_size(rows, cols, rate)) return ZC2D_ERR_CAPACITY;
+  size_t bc = (cols + 3) / 4, br = (rows + 3) / 4;
+  for (size_t bi = 0; bi < br; ++bi)
+    for (size_t bj = 0; bj < bc; ++bj) {
+      size_t at = (bi * bc + bj) * (size_t)(2 * rate);
+      float s[16], d[16];
+      zc2d_ref_decode_block((const uint8_t *)in[0] + at, rate, s);
+      for (int c = 1; c < k; ++c) {
+        zc2d_ref_decode_block((const uint8_t *)in[c] + at, rate, d);
+        for (int i = 0; i < 16; ++i) {
+          volatile float t = s[i] + d[i]; /* one fp32 rounding per add */
+          s[i] = t;
+        }
+      }
+      size_t rv = rows - 4 * bi < 4 ? rows - 4 * bi : 4, cv = cols - 4 * bj < 4 ? cols - 4 * bj : 4;
+      float f[16];
+      for (size_t r = 0; r < 4; ++r)
+        for (size_t q = 0; q < 4; ++q) f[4 * r + q] = s[4 * (r < rv ? r : rv - 1) + (q < cv ? q : cv - 1)];
+      zc2d_ref_encode_block(f, rate, (uint8_t *)out + at);
     }
   return ZC2D_OK;
 }

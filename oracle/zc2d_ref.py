@@ -36,6 +36,8 @@ def lib():
                                         ctypes.c_void_p, ctypes.c_size_t]
         L.zc2d_ref_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
                                           ctypes.c_void_p]
+        L.zc2d_ref_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t,
+                                                 ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
         _ready = True
     return L
 
@@ -115,4 +117,19 @@ def decompress(stream, rows, cols, rate):
     rc = lib().zc2d_ref_decompress(s.ctypes.data, rows, cols, int(rate), out.ctypes.data)
     if rc != 0:
         raise ValueError("zc2d_ref_decompress failed: %d" % rc)
+    return out
+
+
+def reduce_compressed(streams, rows, cols, rate):
+    ss = [np.ascontiguousarray(s, dtype=np.uint8) for s in streams]
+    size = compressed_size(rows, cols, rate)
+    for s in ss:
+        if s.size < size:
+            raise ValueError("stream too short")
+    k = len(ss)
+    ptrs = (ctypes.c_void_p * max(k, 1))(*[s.ctypes.data for s in ss])
+    out = np.zeros(size, dtype=np.uint8)
+    rc = lib().zc2d_ref_reduce_compressed(ptrs, k, int(rows), int(cols), int(rate), out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError("zc2d_ref_reduce_compressed failed: %d" % rc)
     return out

@@ -201,3 +201,41 @@ def test_arbitrary_bytes_decode(o2):
             a = o2.decompress(s, 32, 64, rate)
             b = o2.decompress(s.copy(), 32, 64, rate)
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.parametrize("shape", [(8, 12), (7, 10), (1, 1), (33, 5)])
+def test_reduce_is_decode_add_encode(o2, shape):
+    """The fused reduce against its definition spelled out with numpy fp32 adds: decode
+    every input, add in order with one rounding per add, compress the sum (which refills
+    the blocks at the matrix edge from the sum itself)."""
+    from paper_2409_02423_amd import workloads
+    rows, cols = shape
+    for rate in (2, 4, 8, 16):
+        for k in (1, 2, 3, 8):
+            comp = [o2.compress(workloads.gradient_lowrank(rows, cols, config=5, index=j).reshape(rows, cols) * np.float32(1 + j), rate)
+                    for j in range(k)]
+            total = o2.decompress(comp[0], rows, cols, rate)
+            for c in comp[1:]:
+                total = (total + o2.decompress(c, rows, cols, rate)).astype(np.float32)
+            want = o2.compress(total, rate)
+            got = o2.reduce_compressed(comp, rows, cols, rate)
+            assert np.array_equal(got, want), (shape, rate, k)
+    with pytest.raises(ValueError):
+        o2.reduce_compressed([], rows, cols, 4)
+    with pytest.raises(ValueError):
+        o2.reduce_compressed([comp[0]] * 17, rows, cols, 16)
+
+
+def test_reduce_edge_fill_comes_from_the_sum(o2):
+    """A 2 x 2 matrix in one block: the two inputs decode to different fills than the fill of
+    their sum; the reduce must encode the block whose fill repeats the summed values."""
+    a = np.array([[1.0, 2.0], [3.0, 5.0]], dtype=np.float32)
+    b = np.array([[0.5, -2.0], [1.0, 0.25]], dtype=np.float32)
+    ca, cb = o2.compress(a, 16), o2.compress(b, 16)
+    got = o2.reduce_compressed([ca, cb], 2, 2, 16)
+    total = (o2.decompress(ca, 2, 2, 16) + o2.decompress(cb, 2, 2, 16)).astype(np.float32)
+    assert np.array_equal(got, o2.compress(total, 16))
+    full = o2.decode_block(got, 16).reshape(4, 4)
+    assert np.allclose(full[:2, :2], a + b, rtol=1e-3)
+    assert np.allclose(full[2:, :2], np.broadcast_to((a + b)[1], (2, 2)), rtol=1e-3)      # last row repeated
+    assert np.allclose(full[:2, 2:], np.broadcast_to((a + b)[:, 1:], (2, 2)), rtol=1e-3)  # last column repeated
