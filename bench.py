@@ -243,13 +243,16 @@ def main():
         torch.cuda.synchronize()
         tc = float(np.median([m[0].elapsed_time(m[1]) for m in m2[2:]]))
         td = float(np.median([m[1].elapsed_time(m[2]) for m in m2[2:]]))
+        rm = torch.empty_like(cm)
+        tr = float(np.median(time_events(lambda: zc.zc2d_reduce_compressed([cm, cm], m_rows, m_cols, r2, d_out=rm), 12, torch)[2:]))
+        del rm
         mb = 4 * n + cm.numel()
         rel2 = float(((ym - xm).double().pow(2).mean() / xm.double().pow(2).mean()).sqrt())
         one = zc.zc_decompress(zc.zc_compress(xm.reshape(-1), r2), n, r2)
         rel1 = float(((one - xm.reshape(-1)).double().pow(2).mean() / xm.double().pow(2).mean()).sqrt())
         del one, cm
         blocks_4x4["rate_%d" % r2] = {
-            "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+            "compress_ms": round(tc, 4), "decompress_ms": round(td, 4), "reduce_2way_ms": round(tr, 4),
             "compress_hbm_frac": round(mb / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "decompress_hbm_frac": round(mb / (td * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "relative_rms_error": round(rel2, 5), "relative_rms_error_blocks_of_4": round(rel1, 5)}

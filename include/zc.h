@@ -166,6 +166,16 @@ int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d
  * must not overlap d_in. */
 int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream);
 
+/* The reduce-scatter step (Sec. IV-A) on matrix-shaped messages: d_in is a HOST array of
+ * k device pointers (k in [1, 16]) to compressed matrices of the same shape and rate.
+ * Writes to d_out the compressed form of the element-wise fp32 sum ((x_0 + x_1) + x_2) +
+ * ... of the decompressed matrices; only the k inputs and the output touch device memory.
+ * The pointer array is read before the call returns.  d_out may be the same buffer as one
+ * of the inputs (each block is read before it is written) but must not partially overlap
+ * any. */
+int zc2d_reduce_compressed(const void* const* d_in, int k, size_t rows, size_t cols, int rate, void* d_out,
+                           size_t out_cap, void* stream);
+
 /*
  * Lossless messages, format "ZL-1": the role the paper's first hybrid scheme gives to a
  * lossless codec of the MPC kind on model-parallel traffic (Sec. II-A, Sec. III-A and its

@@ -207,6 +207,74 @@ __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* _
   }
 }
 
+struct ChunkPointers2d {
+  const uint8_t* p[16];
+};
+
+// The reduce-scatter step on matrix-shaped messages: block b of the k chunks is decoded,
+// the 16 values are added in registers in chunk order, and the sum is encoded; where the
+// block sticks out of the matrix its fill is taken from the sum's last valid row / column.
+template <int RATE>
+__global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chunks, int k, Walk w, uint8_t* out) {
+  __shared__ __attribute__((aligned(16))) uint32_t expand[256];
+  __shared__ __attribute__((aligned(16))) uint32_t token[1 << zc2d::kLookahead];
+  for (int i = threadIdx.x; i < 256 / 4; i += kThreads)
+    reinterpret_cast<uint4*>(expand)[i] = reinterpret_cast<const uint4*>(g_expand.v)[i];
+  stage_table<(1 << zc2d::kLookahead)>(g_token.v, token);   // (its barrier covers both tables)
+  constexpr int NW = zc2d::Traits<RATE>::kWords;
+  const size_t b0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (b0 >= w.blocks) return;
+  Cursor cur;
+  cur.start(w, b0);
+  for (;;) {
+    const size_t at = cur.b * zc2d::Traits<RATE>::kBlockBytes;
+    float sum[16];
+    {
+      uint32_t W[NW];
+      load_words<NW>(chunks.p[0] + at, W);
+      zc2d::decode_block<RATE>(W, token, sum, AnyLane());
+    }
+#pragma unroll 1
+    for (int j = 1; j < k; ++j) {
+      uint32_t W[NW];
+      float y[16];
+      load_words<NW>(chunks.p[j] + at, W);
+      zc2d::decode_block<RATE>(W, token, y, AnyLane());
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sum[i] += y[i];
+    }
+    uint32_t x[16];
+    if (cur.whole(w) || (4 * cur.bi + 4 <= w.rows && 4 * cur.bj + 4 <= w.cols)) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) x[i] = __float_as_uint(sum[i]);
+    } else {
+      const uint32_t rv = (uint32_t)(w.rows - 4 * cur.bi < 4 ? w.rows - 4 * cur.bi : 4);
+      const uint32_t cv = (uint32_t)(w.cols - 4 * cur.bj < 4 ? w.cols - 4 * cur.bj : 4);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          // value at (min(r, rv-1), min(q, cv-1)), picked without indexing registers by a variable
+          float v = sum[0];
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+              const bool pick = (uint32_t)rr == ((uint32_t)r < rv ? (uint32_t)r : rv - 1) &&
+                                (uint32_t)qq == ((uint32_t)q < cv ? (uint32_t)q : cv - 1);
+              v = pick ? sum[4 * rr + qq] : v;
+            }
+          x[4 * r + q] = __float_as_uint(v);
+        }
+    }
+    uint32_t W[NW];
+    zc2d::encode_block<RATE>(x, expand, W, AnyLane());
+    store_words<NW>(out + at, W);
+    cur.advance(w);
+    if (cur.b >= w.blocks) break;
+  }
+}
+
 int compute_units() {
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 256;
@@ -295,6 +363,32 @@ int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float*
   const unsigned grid = grid_for(blocks);
   const Walk w = walk_for(rows, cols, grid);
 #define CALL(R) hipLaunchKernelGGL(decompress2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), w, d_out)
+  ZC2D_DISPATCH_RATE(rate, CALL)
+#undef CALL
+  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+
+int zc2d_reduce_compressed(const void* const* d_in, int k, size_t rows, size_t cols, int rate, void* d_out,
+                           size_t out_cap, void* stream) {
+  if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
+  if (k < 1 || k > 16) return ZC_ERR_K;
+  if (rows == 0 || cols == 0) return ZC_OK;
+  if (!d_in || !d_out) return ZC_ERR_NULL;
+  ChunkPointers2d chunks;
+  for (int j = 0; j < 16; ++j) chunks.p[j] = nullptr;
+  for (int j = 0; j < k; ++j) {
+    if (!d_in[j]) return ZC_ERR_NULL;
+    if (!aligned16(d_in[j])) return ZC_ERR_ALIGN;
+    chunks.p[j] = static_cast<const uint8_t*>(d_in[j]);
+  }
+  if (!aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
+  if (out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
+  const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const unsigned grid = grid_for(blocks);
+  const Walk w = walk_for(rows, cols, grid);
+#define CALL(R) hipLaunchKernelGGL(reduce2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, chunks, k, w, static_cast<uint8_t*>(d_out))
   ZC2D_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;

@@ -21,7 +21,7 @@ ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE 
 EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
            "zc_compress_half", "zc_decompress_half",
-           "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress",
+           "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress", "zc2d_reduce_compressed",
            "zl_max_compressed_size", "zl_compress", "zl_stream_bytes", "zl_decompress")
 
 _lib = None
@@ -72,6 +72,8 @@ def lib():
                                     ctypes.c_size_t, ctypes.c_void_p]
         L.zc2d_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p]
+        L.zc2d_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
+                                             ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.zl_max_compressed_size.restype = ctypes.c_size_t
         L.zl_max_compressed_size.argtypes = [ctypes.c_size_t]
         L.zl_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
@@ -315,6 +317,28 @@ def zc2d_decompress(d_in, rows, cols, rate, d_out=None, stream=None):
                                _stream_handle(stream))
     if rc != ZC_OK:
         raise ZcError(rc, "zc2d_decompress")
+    return d_out
+
+
+def zc2d_reduce_compressed(d_in, rows, cols, rate, d_out=None, stream=None):
+    """List of k uint8 CUDA tensors (compressed matrices of one shape) -> compressed sum."""
+    chunks = list(d_in)
+    need = zc2d_compressed_size(rows, cols, rate)
+    if need == 0 and rows * cols != 0:
+        raise ZcError(ZC_ERR_RATE, "zc2d_reduce_compressed")
+    for c in chunks:
+        _check_device_tensor(c, torch.uint8, "every chunk")
+        if c.numel() < need:
+            raise ValueError("a chunk holds %d bytes, need %d" % (c.numel(), need))
+    if d_out is None:
+        device = chunks[0].device if chunks else torch.device("cuda")
+        d_out = torch.empty(need, dtype=torch.uint8, device=device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    ptrs = (ctypes.c_void_p * max(len(chunks), 1))(*[c.data_ptr() for c in chunks])
+    rc = lib().zc2d_reduce_compressed(ptrs, len(chunks), int(rows), int(cols), int(rate), d_out.data_ptr(), d_out.numel(),
+                                      _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_reduce_compressed")
     return d_out
 
 

@@ -178,6 +178,53 @@ def test_runs_on_a_side_stream(gpu, ref):
     _same_floats(_host(d), ref.decompress(want_c, 512, 2048, 8), "side stream decompress")
 
 
+@pytest.mark.parametrize("rate", RATES)
+def test_reduce_matches_reference(gpu, ref, rate):
+    for rows, cols in ((64, 256), (61, 1027), (3, 5), (1030, 7)):
+        mats = [_matrix(rows, cols, seed=10 + j) * np.float32(1 + j) for j in range(8)]
+        comp = [ref.compress(m, rate) for m in mats]
+        dcomp = [_dev(c) for c in comp]
+        for k in (1, 2, 3, 8):
+            print("2d reduce rate", rate, "shape", rows, cols, "k", k, flush=True)
+            want = ref.reduce_compressed(comp[:k], rows, cols, rate)
+            got = gpu.zc2d_reduce_compressed(dcomp[:k], rows, cols, rate)
+            _same_bytes(_host(got), want, rate, "reduce %dx%d r%d k%d" % (rows, cols, rate, k))
+        # in place over the first input, as a ring step does
+        acc = dcomp[0].clone()
+        gpu.zc2d_reduce_compressed([acc, dcomp[1]], rows, cols, rate, d_out=acc)
+        _same_bytes(_host(acc), ref.reduce_compressed(comp[:2], rows, cols, rate), rate, "reduce in place")
+
+
+def test_reduce_errors(gpu):
+    import torch
+    c = torch.zeros(gpu.zc2d_compressed_size(8, 8, 4), dtype=torch.uint8, device="cuda")
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_reduce_compressed([], 8, 8, 4, d_out=c)
+    assert e.value.code == gpu.ZC_ERR_K
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_reduce_compressed([c] * 17, 8, 8, 4)
+    assert e.value.code == gpu.ZC_ERR_K
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_reduce_compressed([c, c], 8, 8, 4, d_out=c[:16])
+    assert e.value.code == gpu.ZC_ERR_CAPACITY
+    torch.cuda.synchronize()
+
+
+def test_full_size_reduce_sampled(gpu, ref):
+    """Two 8192 x 32768 matrices reduced at rate 4, checked on sampled bands of block rows."""
+    rows, cols, rate = 8192, 32768, 4
+    bc = cols // 4
+    mats = [workloads.gradient_lowrank(rows, cols, config=2, index=j).reshape(rows, cols) for j in range(2)]
+    dcomp = [gpu.zc2d_compress(_dev(m), rate) for m in mats]
+    out = gpu.zc2d_reduce_compressed(dcomp, rows, cols, rate)
+    rng = np.random.default_rng(78)
+    for bi in sorted(set([0, rows // 4 - 1] + [int(b) for b in rng.integers(0, rows // 4, size=4)])):
+        print("2d full size reduce, block row", bi, flush=True)
+        comp = [ref.compress(m[4 * bi: 4 * bi + 4], rate) for m in mats]
+        want = ref.reduce_compressed(comp, 4, cols, rate)
+        _same_bytes(_host(out[bi * bc * 2 * rate: (bi + 1) * bc * 2 * rate]), want, rate, "full reduce block row %d" % bi)
+
+
 def test_full_size_gradient_matrix_sampled(gpu, ref):
     """The matrix the benchmark times the 2-D calls on (8192 x 32768 = 2^28 values with the
     low-rank structure of configuration 2), at the rates it is timed at; the reference
