@@ -133,6 +133,36 @@ constexpr EncTable build_enc_table() {
   return t;
 }
 
+// Encoder at rate 4, whole payload in one step.  Eight bits reach at most the first three
+// non-empty planes in full (the first costs at least 3 bits, each later one at least 2) and
+// of a fourth only the bit of coefficient 0, which comes first.  Index = those 13 bits:
+// four planes of coefficient 0 (earliest plane highest), then three of coefficient 1, of
+// coefficient 2, of coefficient 3.  Entry = the payload byte when the first of these
+// planes is plane 31; with `lead` empty planes before it the payload is the entry shifted
+// up by `lead` (an empty plane costs one zero bit; what no longer fits is cut, as the
+// embedded code allows).  Planes below plane 0 enter the index as zeros and code as zeros,
+// which is what unused payload bits are.
+struct Enc4Table { uint8_t v[1 << 13]; };
+
+constexpr Enc4Table build_enc4_table() {
+  Enc4Table t{};
+  for (int x = 0; x < (1 << 13); ++x) {
+    const int c0 = (x >> 9) & 15, c1 = (x >> 6) & 7, c2 = (x >> 3) & 7, c3 = x & 7;
+    uint32_t code = 0;
+    int len = 0, n = 0;
+    for (int k = 0; k < 4; ++k) {
+      int p = (c0 >> (3 - k)) & 1;
+      if (k < 3) p |= ((c1 >> (2 - k)) & 1) << 1 | ((c2 >> (2 - k)) & 1) << 2 | ((c3 >> (2 - k)) & 1) << 3;
+      const PlaneCode a = code_one_plane(n, p);
+      if (len < 32) code |= a.code << len;
+      len += a.len;
+      n = a.next;
+    }
+    t.v[x] = (uint8_t)(code & 0xFFu);
+  }
+  return t;
+}
+
 // Decoder, one plane per step.  Index = (n*8 + min(bits left, 7))*128 + next 7 stream
 // bits.  Entry = the plane's bit of coefficient i at bit 8*i | bits consumed << 1 |
 // (next state) << 12, which is the byte offset of that state's 8*128 entries.
@@ -195,7 +225,7 @@ constexpr Dec4Table build_dec4_table() {
 
 // Pointers to the staged tables; a kernel sets only those its rate uses.
 struct Tables {
-  const uint32_t* enc;
+  const uint32_t* enc;   // EncTable; at rate 4 the bytes of Enc4Table
   const uint32_t* dec;
   const float* dec4;
 };
@@ -297,6 +327,17 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
   uint32_t left = avail > 0 ? (uint32_t)avail : 0u;
 #pragma unroll
   for (int i = 0; i < 4; ++i) u[i] <<= (lead & 31u);  // top plane to bit 31 (all words are zero if lead = 32)
+  if constexpr (RATE == 4) {
+    uint32_t idx = u[0] >> 28;
+    idx = alignbit(idx, u[1], 29);  // (idx << 3) | top three bits of the next word
+    idx = alignbit(idx, u[2], 29);
+    idx = alignbit(idx, u[3], 29);
+    const uint32_t payload = ((uint32_t) reinterpret_cast<const uint8_t*>(tab.enc)[idx] << (lead & 31u)) & 0xFFu;
+    W[0] = E | payload << 8;
+    (void)left;
+    (void)any_lane_active;
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < NW; ++j) W[j] = 0;
   uint32_t state = 0;  // byte offset of the current state's table rows

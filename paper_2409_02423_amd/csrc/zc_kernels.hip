@@ -18,11 +18,13 @@ namespace {
 __device__ const zc::EncTable g_enc_table = zc::build_enc_table();
 __device__ const zc::DecTable g_dec_table = zc::build_dec_table();
 __device__ const zc::Dec4Table g_dec4_table = zc::build_dec4_table();
+__device__ __align__(16) const zc::Enc4Table g_enc4_table = zc::build_enc4_table();
 
 constexpr int kThreads = 256;          // 4 wavefronts
 constexpr int kEncWords = 5 * 256;
 constexpr int kDecWords = 5 * 8 * 128;
 constexpr int kDec4Words = 256 * 4;
+constexpr int kEnc4Words = (1 << 13) / 4;
 constexpr int kMaxChunks = 16;
 
 struct AnyLane {
@@ -46,6 +48,17 @@ __device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table
     int idx = threadIdx.x + i * kThreads;
     if (idx < kVecs) reinterpret_cast<uint4*>(lds)[idx] = v[i];
   }
+}
+
+// Rate 4 encodes its one payload byte with one look-up in the 8192-entry table; the other
+// rates use the two-planes-per-step table.
+template <int RATE>
+constexpr int encoder_table_words() { return RATE == 4 ? kEnc4Words : kEncWords; }
+
+template <int RATE>
+__device__ __forceinline__ void stage_encoder_table(uint32_t* lds) {
+  if constexpr (RATE == 4) stage_table<kEnc4Words>(lds, reinterpret_cast<const uint32_t*>(g_enc4_table.v));
+  else stage_table<kEncWords>(lds, g_enc_table.v);
 }
 
 // Rate 4 decodes its one payload byte with the 256-entry block table; the other rates
@@ -222,8 +235,8 @@ template <int RATE> constexpr int reduce_unroll() { return 4; }
 template <int RATE, int U, int DT>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restrict__ in, size_t n,
                                                             uint8_t* __restrict__ out) {
-  __shared__ __align__(16) uint32_t enc[kEncWords];
-  stage_table<kEncWords>(enc, g_enc_table.v);
+  __shared__ __align__(16) uint32_t enc[encoder_table_words<RATE>()];
+  stage_encoder_table<RATE>(enc);
   __syncthreads();
   const zc::Tables tab = {enc, nullptr, nullptr};
   constexpr int NW = zc::Traits<RATE>::kWords;
@@ -340,8 +353,8 @@ template <int RATE, int U, bool LOCAL, bool RAW_OUT>
 __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, const float* local, size_t n,
                                                           uint8_t* out, float* out_raw) {
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
-  __shared__ __align__(16) uint32_t enc[RAW_OUT ? 4 : kEncWords];
-  if constexpr (!RAW_OUT) stage_table<kEncWords>(enc, g_enc_table.v);
+  __shared__ __align__(16) uint32_t enc[RAW_OUT ? 4 : encoder_table_words<RATE>()];
+  if constexpr (!RAW_OUT) stage_encoder_table<RATE>(enc);
   const zc::Tables tab = stage_decoder_table<RATE>(dec, enc);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;

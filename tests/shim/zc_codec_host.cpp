@@ -9,14 +9,16 @@ namespace {
 const zc::EncTable kEnc = zc::build_enc_table();
 const zc::DecTable kDec = zc::build_dec_table();
 const zc::Dec4Table kDec4 = zc::build_dec4_table();
+alignas(4) const zc::Enc4Table kEnc4 = zc::build_enc4_table();
 const zc::Tables kTables = {kEnc.v, kDec.v, kDec4.v};
+const zc::Tables kTables4 = {reinterpret_cast<const uint32_t*>(kEnc4.v), kDec.v, kDec4.v};
 auto always = [](bool p) { return p; };
 
 template <int RATE>
 void enc(const float* x, uint8_t* out) {
   uint32_t b[4], W[zc::Traits<RATE>::kWords];
   std::memcpy(b, x, 16);
-  zc::encode_block<RATE>(b, kTables, W, always);
+  zc::encode_block<RATE>(b, RATE == 4 ? kTables4 : kTables, W, always);
   std::memcpy(out, W, zc::Traits<RATE>::kBlockBytes);
 }
 template <int RATE>
