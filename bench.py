@@ -28,7 +28,7 @@ INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one
 # HBM bytes per launch (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, the scale a 1 GiB
 # device copy gives on this machine) and wave-level VALU instructions per launch
 # (SQ_INSTS_VALU; x 64 lanes = lane operations).
-MEASURED_TRAFFIC_BYTES = {"compress": 1216590636, "decompress": 1208160873, "reduce": 402882448}
+MEASURED_TRAFFIC_BYTES = {"compress": 1216294233, "decompress": 1208248851, "reduce": 402916751}
 MEASURED_VALU_WAVE_INSTS = {"compress": 61128704, "decompress": 13762560, "reduce": 86425600}
 
 
