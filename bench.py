@@ -11,7 +11,7 @@ structure, rate 4), synthetic and seeded, resident in HBM before timing starts.
 `value` is GB/s of uncompressed fp32 pushed through the whole step (4*n / step time).
 
 Prints ONE JSON line on stdout.  --sweep adds per-kernel figures for all five
-configurations on stderr (and in gpurun_out/sweep.json when that folder exists).
+configurations on stderr (and in the file given with --sweep-out).
 """
 import argparse
 import json
@@ -99,6 +99,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=26)
     ap.add_argument("--sweep", action="store_true", help="also time every kernel on all five configurations")
+    ap.add_argument("--sweep-out", default=None, help="file that receives the --sweep figures as JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the 1 GiB input (known traffic, for scaling profiler counters)")
     ap.add_argument("--rates", type=int, nargs="+", default=None,
@@ -306,8 +307,8 @@ def main():
     if args.sweep:
         result_sweep = sweep(torch, zc, workloads, dev)
         print(json.dumps(result_sweep, indent=1), file=sys.stderr)
-        if os.path.isdir("gpurun_out"):
-            with open("gpurun_out/sweep.json", "w") as f:
+        if args.sweep_out:
+            with open(args.sweep_out, "w") as f:
                 json.dump(result_sweep, f, indent=1)
 
     if not args.no_cpu_baseline:
