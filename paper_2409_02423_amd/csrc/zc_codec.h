@@ -114,7 +114,13 @@ constexpr PlaneBits read_one_plane(int n, int avail, uint32_t s) {
 // two planes of coefficient 0 (earlier plane in the higher bit), 5:4 of coefficient 1,
 // 3:2 of coefficient 2, 1:0 of coefficient 3.  Entry = code word (bits 13:0) |
 // length << 14 | (byte offset of the next state's 256 entries) << 18.
-struct EncTable { uint32_t v[5 * 256]; };
+//
+// Behind these, 256 entries for eight planes at once when at least three coefficients are
+// significant (a plane is then its four bits as they are, see the decoder's pair table):
+// entry a = the top eight planes of one coefficient, spread so that the plane at bit 7 - p
+// of a lands on stream bit 4*p; coefficient i's entry is shifted up by i.
+constexpr int kEncPlaneEntries = 5 * 256;
+struct EncTable { uint32_t v[kEncPlaneEntries + 256]; };
 
 constexpr EncTable build_enc_table() {
   EncTable t{};
@@ -130,6 +136,11 @@ constexpr EncTable build_enc_table() {
       t.v[n * 256 + x] = (a.code | b.code << a.len) | (uint32_t)(a.len + b.len) << 14 |
                          (uint32_t)(b.next * 256 * 4) << 18;
     }
+  for (uint32_t a = 0; a < 256; ++a) {
+    uint32_t e = 0;
+    for (int p = 0; p < 8; ++p) e |= ((a >> (7 - p)) & 1u) << (4 * p);
+    t.v[kEncPlaneEntries + a] = e;
+  }
   return t;
 }
 
@@ -166,7 +177,15 @@ constexpr Enc4Table build_enc4_table() {
 // Decoder, one plane per step.  Index = (n*8 + min(bits left, 7))*128 + next 7 stream
 // bits.  Entry = the plane's bit of coefficient i at bit 8*i | bits consumed << 1 |
 // (next state) << 12, which is the byte offset of that state's 8*128 entries.
-struct DecTable { uint32_t v[5 * 8 * 128]; };
+//
+// Behind these, 256 entries for two planes at once when at least three coefficients are
+// significant.  A plane is then four stream bits that are the plane's bits as they are
+// (in state 3 the fourth is the group test of the one coefficient left, which is that
+// coefficient's bit), whatever the state becomes.  Index = the next 8 stream bits, those
+// past the budget cleared; entry = for coefficient i, at bit 8*i, its bit of the first
+// plane << 1 | its bit of the second.
+constexpr int kDecPlaneEntries = 5 * 8 * 128;
+struct DecTable { uint32_t v[kDecPlaneEntries + 256]; };
 
 constexpr DecTable build_dec_table() {
   DecTable t{};
@@ -177,6 +196,11 @@ constexpr DecTable build_dec_table() {
         uint32_t spread = (r.p & 1u) | (r.p & 2u) << 7 | (r.p & 4u) << 14 | (r.p & 8u) << 21;
         t.v[(n * 8 + avail) * 128 + s] = spread | (uint32_t)r.used << 1 | (uint32_t)r.next << 12;
       }
+  for (uint32_t b = 0; b < 256; ++b) {
+    uint32_t e = 0;
+    for (int i = 0; i < 4; ++i) e |= ((((b >> i) & 1u) << 1) | ((b >> (4 + i)) & 1u)) << (8 * i);
+    t.v[kDecPlaneEntries + b] = e;
+  }
   return t;
 }
 
@@ -344,6 +368,23 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
 #pragma unroll 1
   for (int step = 0; step < kMaxSteps; ++step) {
     if (!any_lane_active(left > 0)) break;
+    // Once every lane that still has room is in state 3 or 4 (which no lane leaves), planes
+    // are their four bits as they are: eight planes per step, interleaved by four look-ups.
+    // (Planes past plane 0 come out as zeros, which is what unused bits are.)  Not looked for
+    // at rate 8, whose 24 bits end before it pays, nor in the first four planes.
+    if (RATE >= 12 && step >= 2 && !any_lane_active(left > 0 && state < 3u * 256u * 4u)) {
+      const uint32_t* spread = tab.enc + kEncPlaneEntries;
+      const uint32_t code = spread[u[0] >> 24] | spread[u[1] >> 24] << 1 | spread[u[2] >> 24] << 2 | spread[u[3] >> 24] << 3;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) u[i] <<= 8;
+      const uint32_t first = umin(left, 16u);
+      shift_in<NW>(W, code, first);
+      left -= first;
+      const uint32_t second = umin(left, 16u);
+      shift_in<NW>(W, code >> 16, second);
+      left -= second;
+      continue;
+    }
     uint32_t idx = u[0] >> 30;
     idx = alignbit(idx, u[1], 30);  // (idx << 2) | top two bits of the next word
     idx = alignbit(idx, u[2], 30);
@@ -420,19 +461,37 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
 #pragma unroll
     for (int g = 0; g < kGroups; ++g) {
       if (open) {
-        uint32_t acc = 0, m = 0;
-#pragma unroll 1
-        for (; m < 8u; ++m) {
-          if (!any_lane_active(left > 0)) break;
-          const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
-          const uint32_t len = (e >> 1) & 7u;
-          acc = (acc << 1) | (e & 0x01010101u);
-          shift_out<NW>(W, len);
+        if (g > 0 && !any_lane_active(left > 0 && state < 0x3000u)) {
+          // Every lane that still has bits is in state 3 or 4 (which no lane leaves): the
+          // eight planes of this group are the next 32 stream bits, four per plane, as they
+          // are; those past the budget count as zeros.  Looked at between groups only: a
+          // test per plane costs more than it saves at the low rates.
+          uint32_t bits = W[0] >> 2;
+          if constexpr (NW > 1) bits = alignbit(W[1], W[0], 2);
+          const uint32_t len = umin(left, 32u);
+          bits &= len < 32u ? (1u << len) - 1u : 0xFFFFFFFFu;
+          const uint32_t* pair = tab.dec + kDecPlaneEntries;
+          G[g] = pair[bits & 0xFFu] << 6 | pair[(bits >> 8) & 0xFFu] << 4 | pair[(bits >> 16) & 0xFFu] << 2 | pair[bits >> 24];
+          const uint32_t half = umin(len, 16u);
+          shift_out<NW>(W, half);
+          shift_out<NW>(W, len - half);
           left -= len;
-          state = e & 0x7000u;
+          open = any_lane_active(left > 0);
+        } else {
+          uint32_t acc = 0, m = 0;
+#pragma unroll 1
+          for (; m < 8u; ++m) {
+            if (!any_lane_active(left > 0)) break;
+            const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
+            const uint32_t len = (e >> 1) & 7u;
+            acc = (acc << 1) | (e & 0x01010101u);
+            shift_out<NW>(W, len);
+            left -= len;
+            state = e & 0x7000u;
+          }
+          G[g] = acc << (8u - m);
+          open = m == 8u;
         }
-        G[g] = acc << (8u - m);
-        open = m == 8u;
       }
     }
 #pragma unroll

@@ -21,8 +21,8 @@ __device__ const zc::Dec4Table g_dec4_table = zc::build_dec4_table();
 __device__ __align__(16) const zc::Enc4Table g_enc4_table = zc::build_enc4_table();
 
 constexpr int kThreads = 256;          // 4 wavefronts
-constexpr int kEncWords = 5 * 256;
-constexpr int kDecWords = 5 * 8 * 128;
+constexpr int kEncWords = zc::kEncPlaneEntries + 256;
+constexpr int kDecWords = zc::kDecPlaneEntries + 256;
 constexpr int kDec4Words = 256 * 4;
 constexpr int kEnc4Words = (1 << 13) / 4;
 constexpr int kMaxChunks = 16;
