@@ -479,15 +479,36 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
           open = any_lane_active(left > 0);
         } else {
           uint32_t acc = 0, m = 0;
-#pragma unroll 1
-          for (; m < 8u; ++m) {
-            if (!any_lane_active(left > 0)) break;
+          auto one_plane = [&]() {
             const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
             const uint32_t len = (e >> 1) & 7u;
             acc = (acc << 1) | (e & 0x01010101u);
             shift_out<NW>(W, len);
             left -= len;
             state = e & 0x7000u;
+          };
+#pragma unroll 1
+          for (; m < 4u; ++m) {
+            if (!any_lane_active(left > 0)) break;
+            one_plane();
+          }
+          if (m == 4u) {
+            if (RATE >= 12 && !any_lane_active(left > 0 && state < 0x3000u)) {
+              // the same in the middle of a group: its last four planes from 16 stream bits
+              const uint32_t len = umin(left, 16u);
+              const uint32_t bits = (W[0] >> 2) & ((1u << len) - 1u);
+              const uint32_t* pair = tab.dec + kDecPlaneEntries;
+              acc = acc << 4 | pair[bits & 0xFFu] << 2 | pair[bits >> 8];
+              shift_out<NW>(W, len);
+              left -= len;
+              m = 8u;
+            } else {
+#pragma unroll 1
+              for (; m < 8u; ++m) {
+                if (!any_lane_active(left > 0)) break;
+                one_plane();
+              }
+            }
           }
           G[g] = acc << (8u - m);
           open = m == 8u;
