@@ -183,3 +183,27 @@ int zl_ref_decompress(const void *in, size_t in_bytes, size_t n, uint32_t *out) 
   }
   return ZL_OK;
 }
+
+/* ---- 16-bit messages ------------------------------------------------------------------
+ * Half-precision traffic (bf16 or fp16; the paper does not say what its messages hold)
+ * goes through the same format: the message of n 16-bit words v is coded as the n 32-bit
+ * words v << 16.  For bf16 that is the value widened to fp32; for any content it is a
+ * plain embedding, so every pattern comes back.  The empty lower halves cost nothing in
+ * the stream (their planes are zero). */
+
+int zl_ref_compress16(const uint16_t *in, size_t n, void *out, size_t out_cap, size_t *out_bytes,
+                      uint32_t *work /* n words */) {
+  if (n && (!in || !work)) return ZL_ERR_NULL;
+  for (size_t i = 0; i < n; ++i) work[i] = (uint32_t)in[i] << 16;
+  return zl_ref_compress(work, n, out, out_cap, out_bytes);
+}
+
+/* The upper halves of the decoded words (for a stream made by zl_ref_compress16 the lower
+ * halves are zero). */
+int zl_ref_decompress16(const void *in, size_t in_bytes, size_t n, uint16_t *out, uint32_t *work /* n words */) {
+  if (n && (!out || !work)) return ZL_ERR_NULL;
+  int rc = zl_ref_decompress(in, in_bytes, n, work);
+  if (rc != ZL_OK) return rc;
+  for (size_t i = 0; i < n; ++i) out[i] = (uint16_t)(work[i] >> 16);
+  return ZL_OK;
+}

@@ -42,6 +42,9 @@ def lib():
         L.zl_ref_stream_bytes.restype = ctypes.c_size_t
         L.zl_ref_stream_bytes.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
         L.zl_ref_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_void_p]
+        L.zl_ref_compress16.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                        ctypes.POINTER(ctypes.c_size_t), ctypes.c_void_p]
+        L.zl_ref_decompress16.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         _ready = True
     return L
 
@@ -118,4 +121,35 @@ def decompress(stream, n, dtype=np.uint32):
     rc = lib().zl_ref_decompress(s.ctypes.data, s.size, int(n), out.ctypes.data)
     if rc != 0:
         raise StreamError("zl_ref_decompress: %d" % rc)
+    return out.view(dtype)
+
+
+def _halves(x):
+    x = np.ascontiguousarray(x)
+    if x.dtype.itemsize != 2:
+        raise TypeError("16-bit items expected")
+    return x.reshape(-1).view(np.uint16)
+
+
+def compress16(x, guard=0):
+    """Stream for a message of 16-bit items (numpy float16, or uint16 holding bf16 bits)."""
+    h = _halves(x)
+    cap = max_compressed_size(h.size)
+    out = np.full(cap + guard, 0xA5, dtype=np.uint8)
+    work = np.zeros(max(h.size, 1), dtype=np.uint32)
+    size = ctypes.c_size_t(0)
+    rc = lib().zl_ref_compress16(h.ctypes.data, h.size, out.ctypes.data, cap, ctypes.byref(size), work.ctypes.data)
+    if rc != 0:
+        raise StreamError("zl_ref_compress16: %d" % rc)
+    assert (out[size.value:] == 0xA5).all(), "wrote past the stream's end"
+    return out[: size.value].copy()
+
+
+def decompress16(stream, n, dtype=np.uint16):
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    out = np.zeros(int(n), dtype=np.uint16)
+    work = np.zeros(max(int(n), 1), dtype=np.uint32)
+    rc = lib().zl_ref_decompress16(s.ctypes.data, s.size, int(n), out.ctypes.data, work.ctypes.data)
+    if rc != 0:
+        raise StreamError("zl_ref_decompress16: %d" % rc)
     return out.view(dtype)

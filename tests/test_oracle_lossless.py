@@ -217,3 +217,28 @@ def test_malformed_streams_are_rejected(zl):
     t = s.copy(); assert t[H + 16 + 4 * G + 3] & 0x7F != 0x7F                     # values of one magnitude: upper planes absent
     t[H + 16 + 4 * G + 3] |= 0x7F; bad(t)                                         # bitmap promises more planes than stored
     t = s.copy(); t[16:24].view(np.uint64)[0] += np.uint64(8); bad(t)       # total beyond the buffer
+
+
+def test_16_bit_messages(zl):
+    """A 16-bit message is coded as its words shifted into the upper halves: the stream is that
+    of the 32-bit message (for bf16: of the values widened to fp32, which numpy confirms through
+    its own float32 -> bf16 truncation), every 16-bit pattern comes back, and the empty lower
+    halves cost nothing."""
+    every = np.arange(65536, dtype=np.uint16)
+    s = zl.compress16(every, guard=16)
+    assert np.array_equal(s, zl.compress(every.astype(np.uint32) << np.uint32(16)))
+    assert np.array_equal(zl.decompress16(s, every.size), every)
+    r = _rng(9)
+    f = (workloads.activation_gelu(3 * C + 77) * np.float32(3.0)).astype(np.float32)
+    bf = (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16)                 # bf16 by truncation
+    widened = (bf.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    assert np.array_equal(zl.compress16(bf), zl.compress(widened))
+    assert np.array_equal(zl.decompress(zl.compress16(bf), bf.size, dtype=np.float32).view(np.uint32), widened.view(np.uint32))
+    h = f.astype(np.float16)
+    sh = zl.compress16(h)
+    assert np.array_equal(zl.decompress16(sh, h.size, dtype=np.float16).view(np.uint16), h.view(np.uint16))
+    # per value: 16 bits in, at most 16 planes + reference + bitmap out; similar magnitudes drop some more
+    assert sh.size < 2 * h.size * (16 + 2) / 16 + 64 and zl.compress16(bf).size < 2 * bf.size
+    assert zl.compress16(np.zeros(0, dtype=np.uint16)).size == 32
+    odd = r.integers(0, 65536, size=C + 5, dtype=np.uint16)
+    assert np.array_equal(zl.decompress16(zl.compress16(odd), odd.size), odd)
