@@ -212,6 +212,17 @@ int zl_stream_bytes(const void* d_stream, size_t* h_bytes, void* stream);
  * ZC_ERR_CAPACITY if in_bytes cannot even hold the header and table for n words. */
 int zl_decompress(const void* d_in, size_t in_bytes, size_t n, void* d_out, void* stream);
 
+/* 16-bit messages (bf16, fp16 or anything else of that width; the paper does not state what
+ * its messages hold): d_in holds n 16-bit words, which are coded as the n 32-bit words
+ * v << 16, so the stream is an ordinary ZL-1 stream of n words (for bf16: of the values
+ * widened to fp32) and every pattern comes back.  The empty lower halves cost nothing in the
+ * stream.  Otherwise as zl_compress. */
+int zl_compress16(const void* d_in, size_t n, void* d_out, size_t out_cap, void* stream);
+
+/* As zl_decompress, but writes the upper halves of the n decoded words to d_out (n 16-bit
+ * words); for a stream made by zl_compress16 the lower halves are zero. */
+int zl_decompress16(const void* d_in, size_t in_bytes, size_t n, void* d_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -157,21 +157,80 @@ __device__ bool bytes_before(uint64_t* table, const uint64_t* flaw, uint32_t c, 
   return true;
 }
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 // The lane's group of chunk c: words 1024*t + 4*tid .. +3 of the chunk, t = 0..7; words
-// past the end of the message read as zero.
-__device__ __forceinline__ void load_group(const uint32_t* __restrict__ in, size_t n, uint32_t c, int tid, uint32_t (&w)[32]) {
+// past the end of the message read as zero.  HALF: the message holds 16-bit words, which
+// are coded as the 32-bit words v << 16.
+template <bool HALF>
+__device__ __forceinline__ void load_group(const void* __restrict__ message, size_t n, uint32_t c, int tid, uint32_t (&w)[32]) {
   const size_t base = (size_t)c * zl::kChunkWords;
-  if (base + zl::kChunkWords <= n) {
+  if constexpr (HALF) {
+    const uint16_t* in = static_cast<const uint16_t*>(message);
+    if (base + zl::kChunkWords <= n) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + base + 1024 * t + 4 * tid));
-      w[4 * t] = v.x; w[4 * t + 1] = v.y; w[4 * t + 2] = v.z; w[4 * t + 3] = v.w;
+      for (int t = 0; t < 8; ++t) {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(in + base + 1024 * t + 4 * tid));
+        w[4 * t] = v.x << 16; w[4 * t + 1] = v.x & 0xFFFF0000u; w[4 * t + 2] = v.y << 16; w[4 * t + 3] = v.y & 0xFFFF0000u;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const size_t i = base + 1024 * (j >> 2) + 4 * tid + (j & 3);
+        w[j] = i < n ? (uint32_t)in[i] << 16 : 0u;
+      }
     }
   } else {
+    const uint32_t* in = static_cast<const uint32_t*>(message);
+    if (base + zl::kChunkWords <= n) {
 #pragma unroll
-    for (int j = 0; j < 32; ++j) {
-      const size_t i = base + 1024 * (j >> 2) + 4 * tid + (j & 3);
-      w[j] = i < n ? in[i] : 0u;
+      for (int t = 0; t < 8; ++t) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + base + 1024 * t + 4 * tid));
+        w[4 * t] = v.x; w[4 * t + 1] = v.y; w[4 * t + 2] = v.z; w[4 * t + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const size_t i = base + 1024 * (j >> 2) + 4 * tid + (j & 3);
+        w[j] = i < n ? in[i] : 0u;
+      }
+    }
+  }
+}
+
+// The reverse; HALF keeps the upper halves of the words.
+template <bool HALF>
+__device__ __forceinline__ void store_group(void* __restrict__ message, size_t n, uint32_t c, int tid, const uint32_t (&w)[32]) {
+  const size_t base = (size_t)c * zl::kChunkWords;
+  if constexpr (HALF) {
+    uint16_t* out = static_cast<uint16_t*>(message);
+    if (base + zl::kChunkWords <= n) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const u32x2 v = {w[4 * t] >> 16 | (w[4 * t + 1] & 0xFFFF0000u), w[4 * t + 2] >> 16 | (w[4 * t + 3] & 0xFFFF0000u)};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(out + base + 1024 * t + 4 * tid));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const size_t i = base + 1024 * (j >> 2) + 4 * tid + (j & 3);
+        if (i < n) out[i] = (uint16_t)(w[j] >> 16);
+      }
+    }
+  } else {
+    uint32_t* out = static_cast<uint32_t*>(message);
+    if (base + zl::kChunkWords <= n) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const u32x4 v = {w[4 * t], w[4 * t + 1], w[4 * t + 2], w[4 * t + 3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + base + 1024 * t + 4 * tid));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const size_t i = base + 1024 * (j >> 2) + 4 * tid + (j & 3);
+        if (i < n) out[i] = w[j];
+      }
     }
   }
 }
@@ -183,7 +242,8 @@ struct Coded {
   Places at;
 };
 
-__global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* __restrict__ in, size_t n, uint8_t* out,
+template <bool HALF>
+__global__ __launch_bounds__(kThreads) void zl_compress_kernel(const void* __restrict__ in, size_t n, uint8_t* out,
                                                                uint32_t chunks) {
   __shared__ uint32_t stage[kWaveStageWords * (kThreads / 64)];
   __shared__ uint32_t wave_totals[kThreads / 64];
@@ -214,7 +274,7 @@ __global__ __launch_bounds__(kThreads) void zl_compress_kernel(const uint32_t* _
     const bool coding = c < chunks;
     Coded now;
     if (coding) {
-      load_group(in, n, c, tid, now.planes);
+      load_group<HALF>(in, n, c, tid, now.planes);
       now.bitmap = zl::to_planes(now.planes, now.reference);
       now.chunk = c;
       now.at = workgroup_places((uint32_t)__builtin_popcount(now.bitmap), wave_totals);
@@ -287,8 +347,9 @@ __global__ void zl_finish_kernel(uint8_t* out, size_t n, uint32_t chunks) {
 }
 
 // in_bytes: size of the buffer that holds the stream; every read stays below it.
+template <bool HALF>
 __global__ __launch_bounds__(kThreads) void zl_decompress_kernel(const uint8_t* __restrict__ in, size_t in_bytes, size_t n,
-                                                                 uint32_t* __restrict__ out, uint32_t chunks) {
+                                                                 void* __restrict__ out, uint32_t chunks) {
   __shared__ uint32_t stage[zl::kChunkWords + zl::kChunkWords / 32 + 64];   // spare words as in staged(); a lane may look one past its last plane
   __shared__ uint32_t wave_totals[kThreads / 64];
   const uint64_t* table = reinterpret_cast<const uint64_t*>(in + zl::kHeaderBytes);
@@ -329,21 +390,7 @@ __global__ __launch_bounds__(kThreads) void zl_decompress_kernel(const uint8_t* 
     pos += present ? 1u : 0u;
   }
   zl::from_planes(p, reference);
-
-  const size_t base = (size_t)c * zl::kChunkWords;
-  if (base + zl::kChunkWords <= n) {
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const u32x4 v = {p[4 * t], p[4 * t + 1], p[4 * t + 2], p[4 * t + 3]};
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + base + 1024 * t + 4 * tid));
-    }
-  } else {
-#pragma unroll
-    for (int j = 0; j < 32; ++j) {
-      const size_t i = base + 1024 * (j >> 2) + 4 * tid + (j & 3);
-      if (i < n) out[i] = p[j];
-    }
-  }
+  store_group<HALF>(out, n, c, tid, p);
 }
 
 int compute_units() {
@@ -373,14 +420,9 @@ size_t chunks_of(size_t n) { return (n + zl::kChunkWords - 1) / zl::kChunkWords;
 
 }  // namespace
 
-extern "C" {
-
-size_t zl_max_compressed_size(size_t n) {
-  if (n > kMaxWords) return 0;
-  return zl::kHeaderBytes + chunks_of(n) * (size_t)(8 + zl::kFixedChunkBytes + 4 * zl::kChunkWords);
-}
-
-int zl_compress(const void* d_in, size_t n, void* d_out, size_t out_cap, void* stream) {
+namespace {
+template <bool HALF>
+int launch_zl_compress(const void* d_in, size_t n, void* d_out, size_t out_cap, void* stream) {
   if (!d_out || (n && !d_in)) return ZC_ERR_NULL;
   if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
   if (n > kMaxWords) return ZC_ERR_SIZE;
@@ -399,11 +441,40 @@ int zl_compress(const void* d_in, size_t n, void* d_out, size_t out_cap, void* s
   if (hipGetLastError() != hipSuccess) return ZC_ERR_LAUNCH;
   const size_t resident = (size_t)compute_units() * workgroups_per_cu();
   const unsigned grid = (unsigned)(chunks < resident ? chunks : resident);
-  hipLaunchKernelGGL(zl_compress_kernel, dim3(grid), dim3(kThreads), 0, s, static_cast<const uint32_t*>(d_in), n,
-                     static_cast<uint8_t*>(d_out), (uint32_t)chunks);
+  hipLaunchKernelGGL(zl_compress_kernel<HALF>, dim3(grid), dim3(kThreads), 0, s, d_in, n, static_cast<uint8_t*>(d_out),
+                     (uint32_t)chunks);
   if (hipGetLastError() != hipSuccess) return ZC_ERR_LAUNCH;
   hipLaunchKernelGGL(zl_finish_kernel, dim3(1), dim3(64), 0, s, static_cast<uint8_t*>(d_out), n, (uint32_t)chunks);
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+
+template <bool HALF>
+int launch_zl_decompress(const void* d_in, size_t in_bytes, size_t n, void* d_out, void* stream) {
+  if (!d_in || (n && !d_out)) return ZC_ERR_NULL;
+  if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
+  if (n > kMaxWords) return ZC_ERR_SIZE;
+  const size_t chunks = chunks_of(n);
+  if (in_bytes < zl::kHeaderBytes + 8 * chunks) return ZC_ERR_CAPACITY;
+  if (chunks == 0) return ZC_OK;
+  hipLaunchKernelGGL(zl_decompress_kernel<HALF>, dim3((unsigned)chunks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint8_t*>(d_in), in_bytes, n, d_out, (uint32_t)chunks);
+  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+}  // namespace
+
+extern "C" {
+
+size_t zl_max_compressed_size(size_t n) {
+  if (n > kMaxWords) return 0;
+  return zl::kHeaderBytes + chunks_of(n) * (size_t)(8 + zl::kFixedChunkBytes + 4 * zl::kChunkWords);
+}
+
+int zl_compress(const void* d_in, size_t n, void* d_out, size_t out_cap, void* stream) {
+  return launch_zl_compress<false>(d_in, n, d_out, out_cap, stream);
+}
+
+int zl_compress16(const void* d_in, size_t n, void* d_out, size_t out_cap, void* stream) {
+  return launch_zl_compress<true>(d_in, n, d_out, out_cap, stream);
 }
 
 int zl_stream_bytes(const void* d_stream, size_t* h_bytes, void* stream) {
@@ -418,15 +489,11 @@ int zl_stream_bytes(const void* d_stream, size_t* h_bytes, void* stream) {
 }
 
 int zl_decompress(const void* d_in, size_t in_bytes, size_t n, void* d_out, void* stream) {
-  if (!d_in || (n && !d_out)) return ZC_ERR_NULL;
-  if (!aligned16(d_in) || !aligned16(d_out)) return ZC_ERR_ALIGN;
-  if (n > kMaxWords) return ZC_ERR_SIZE;
-  const size_t chunks = chunks_of(n);
-  if (in_bytes < zl::kHeaderBytes + 8 * chunks) return ZC_ERR_CAPACITY;
-  if (chunks == 0) return ZC_OK;
-  hipLaunchKernelGGL(zl_decompress_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const uint8_t*>(d_in), in_bytes, n, static_cast<uint32_t*>(d_out), (uint32_t)chunks);
-  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+  return launch_zl_decompress<false>(d_in, in_bytes, n, d_out, stream);
+}
+
+int zl_decompress16(const void* d_in, size_t in_bytes, size_t n, void* d_out, void* stream) {
+  return launch_zl_decompress<true>(d_in, in_bytes, n, d_out, stream);
 }
 
 }  // extern "C"

@@ -22,7 +22,7 @@ EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class"
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
            "zc_compress_half", "zc_decompress_half",
            "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress", "zc2d_reduce_compressed",
-           "zl_max_compressed_size", "zl_compress", "zl_stream_bytes", "zl_decompress")
+           "zl_max_compressed_size", "zl_compress", "zl_stream_bytes", "zl_decompress", "zl_compress16", "zl_decompress16")
 
 _lib = None
 
@@ -79,6 +79,8 @@ def lib():
         L.zl_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.zl_stream_bytes.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t), ctypes.c_void_p]
         L.zl_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.zl_compress16.argtypes = L.zl_compress.argtypes
+        L.zl_decompress16.argtypes = L.zl_decompress.argtypes
         _lib = L
     return _lib
 
@@ -388,4 +390,37 @@ def zl_decompress(d_in, n, d_out=None, dtype=torch.float32, stream=None):
     rc = lib().zl_decompress(d_in.data_ptr(), d_in.numel(), int(n), d_out.data_ptr(), _stream_handle(stream))
     if rc != ZC_OK:
         raise ZcError(rc, "zl_decompress")
+    return d_out
+
+
+def _check_halves(t, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.element_size() == 2 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of 16-bit items" % what)
+
+
+def zl_compress16(d_in, d_out=None, stream=None):
+    """CUDA tensor of 16-bit items (bfloat16, float16, int16) -> uint8 CUDA tensor that starts with the
+    lossless stream of the items taken as the upper halves of 32-bit words."""
+    _check_halves(d_in, "d_in")
+    n = d_in.numel()
+    if d_out is None:
+        d_out = torch.empty(zl_max_compressed_size(n), dtype=torch.uint8, device=d_in.device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zl_compress16(d_in.data_ptr(), n, d_out.data_ptr(), d_out.numel(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zl_compress16")
+    return d_out
+
+
+def zl_decompress16(d_in, n, d_out=None, dtype=torch.bfloat16, stream=None):
+    """Lossless stream -> the upper halves of its n words as 16-bit items."""
+    _check_device_tensor(d_in, torch.uint8, "d_in")
+    if d_out is None:
+        d_out = torch.empty(int(n), dtype=dtype, device=d_in.device)
+    _check_halves(d_out, "d_out")
+    if d_out.numel() < n:
+        raise ValueError("d_out holds %d items, need %d" % (d_out.numel(), n))
+    rc = lib().zl_decompress16(d_in.data_ptr(), d_in.numel(), int(n), d_out.data_ptr(), _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zl_decompress16")
     return d_out

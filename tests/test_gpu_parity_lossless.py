@@ -128,6 +128,34 @@ def test_errors_and_side_stream(gpu, ref):
     _same(_host(y).view(np.uint32), _host(x).view(np.uint32), "side stream round trip")
 
 
+@pytest.mark.parametrize("n", [0, 1, 5, C - 3, C, 5 * C + 1234, 65536])
+def test_16_bit_messages(gpu, ref, n):
+    """bf16 activations, fp16 activations and arbitrary 16-bit patterns: stream and round trip
+    against the reference, and the stream read back as 32-bit words."""
+    import torch
+    rng = np.random.default_rng(n + 1)
+    f = workloads.activation_gelu(max(n, 1), config=3, index=2)[:n]
+    cases = {"bf16": (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16),
+             "fp16": f.astype(np.float16).view(np.uint16),
+             "bits": np.arange(n, dtype=np.uint32).astype(np.uint16) if n == 65536 else rng.integers(0, 65536, size=n, dtype=np.uint16)}
+    for name, h in cases.items():
+        print("lossless 16-bit", name, "n", n, flush=True)
+        want = ref.compress16(h)
+        cap = gpu.zl_max_compressed_size(n)
+        out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        gpu.zl_compress16(_dev(h.view(np.int16)), d_out=out[:cap])
+        size = gpu.zl_stream_bytes(out)
+        hh = _host(out)
+        _same(hh[:size], want, "16-bit stream %s n=%d" % (name, n))
+        assert (hh[cap:] == 0xA5).all()
+        back = torch.full((n + 32,), -7, dtype=torch.int16, device="cuda")
+        gpu.zl_decompress16(out[:size], n, d_out=back[:n])
+        _same(_host(back[:n]).view(np.uint16), h, "16-bit round trip %s n=%d" % (name, n))
+        assert (_host(back[n:]) == -7).all()
+        words = gpu.zl_decompress(out[:size], n, dtype=torch.int32)
+        _same(_host(words).view(np.uint32), h.astype(np.uint32) << np.uint32(16), "16-bit stream as words %s" % name)
+
+
 def test_two_compressions_at_once(gpu, ref):
     """Two messages compressed on two streams at the same time (each kernel alone would fill
     the chip): both streams must come out as the reference's, several times over."""
