@@ -243,7 +243,7 @@ struct Coded {
 };
 
 template <bool HALF>
-__global__ __launch_bounds__(kThreads) void zl_compress_kernel(const void* __restrict__ in, size_t n, uint8_t* out,
+__global__ __launch_bounds__(kThreads, 4) void zl_compress_kernel(const void* __restrict__ in, size_t n, uint8_t* out,
                                                                uint32_t chunks) {
   __shared__ uint32_t stage[kWaveStageWords * (kThreads / 64)];
   __shared__ uint32_t wave_totals[kThreads / 64];
