@@ -1,0 +1,101 @@
+"""Messages of more than 2^32 values: block, chunk and byte offsets beyond 32 bits.  Inputs are
+filled on the GPU by torch's seeded generator; the reference recomputes slices that are copied
+back, at the start, across the 2^32 boundary and at the ragged end."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _fill(n, seed):
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    for s in range(0, n, step):
+        e = min(n, s + step)
+        x[s:e].normal_(0.0, 1e-3, generator=g)
+    return x
+
+
+def _host(t):
+    return t.cpu().numpy()
+
+
+def test_one_dimensional_beyond_2_to_32(oracle):
+    import torch
+    from paper_2409_02423_amd import zc
+    n = (1 << 32) + 4099
+    x = _fill(n, 1)
+    for rate in (4, 16):
+        bb = rate // 2
+        c = zc.zc_compress(x, rate)
+        assert c.numel() == zc.zc_compressed_size(n, rate) == ((n + 3) // 4) * bb
+        y = zc.zc_decompress(c, n, rate)
+        r = zc.zc_reduce_compressed([c, c], n, rate)
+        blocks = (n + 3) // 4
+        for b0, count in ((0, 4096), ((1 << 30) - 2048, 4096), (blocks - 4096, 4096)):
+            print("large 1-D rate", rate, "blocks from", b0, flush=True)
+            lo, hi = 4 * b0, min(n, 4 * (b0 + count))
+            xs = _host(x[lo:hi])
+            want = oracle.compress(xs, rate)
+            assert np.array_equal(_host(c[b0 * bb:(b0 + count) * bb]), want), (rate, b0)
+            assert np.array_equal(_host(y[lo:hi]).view(np.uint32), oracle.decompress(want, xs.size, rate).view(np.uint32))
+            assert np.array_equal(_host(r[b0 * bb:(b0 + count) * bb]), oracle.reduce_compressed([want, want], xs.size, rate))
+        del c, y, r
+    del x
+    torch.cuda.empty_cache()
+
+
+def test_matrix_beyond_2_to_32():
+    import torch
+    from oracle import zc2d_ref
+    from paper_2409_02423_amd import zc
+    rows, cols, rate = 65538, 65540, 4            # 4.3e9 values; the last block row is ragged
+    x = _fill(rows * cols, 2).view(rows, cols)
+    c = zc.zc2d_compress(x, rate)
+    bc = (cols + 3) // 4
+    assert c.numel() == zc.zc2d_compressed_size(rows, cols, rate) == ((rows + 3) // 4) * bc * 2 * rate
+    y = zc.zc2d_decompress(c, rows, cols, rate)
+    for bi in (0, 16383, (rows + 3) // 4 - 1):   # value index 2^32 lies in block row 16383; the last block row is ragged
+        print("large matrix, block row", bi, flush=True)
+        r0, r1 = 4 * bi, min(rows, 4 * bi + 4)
+        xs = _host(x[r0:r1])
+        want = zc2d_ref.compress(xs, rate)
+        assert np.array_equal(_host(c[bi * bc * 2 * rate:(bi + 1) * bc * 2 * rate]), want), bi
+        assert np.array_equal(_host(y[r0:r1]).view(np.uint32), zc2d_ref.decompress(want, r1 - r0, cols, rate).view(np.uint32)), bi
+    del x, c, y
+    torch.cuda.empty_cache()
+
+
+def test_lossless_beyond_2_to_32():
+    import torch
+    from oracle import zl_ref
+    from paper_2409_02423_amd import zc
+    C = 8192
+    n = (1 << 32) + 3 * C + 17
+    x = _fill(n, 3)
+    c = zc.zl_compress(x)
+    size = zc.zl_stream_bytes(c)
+    assert size > 1 << 33                                     # the stream itself is longer than 2^33 bytes
+    y = zc.zl_decompress(c[:size], n)
+    chunks = (n + C - 1) // C
+    table = c[32:32 + 8 * chunks].view(torch.int64)
+    ends = table & ((1 << 62) - 1)
+    assert bool(((table >> 62) & 3 == 2).all()) and int(ends[-1]) == size - 32 - 8 * chunks
+    step = 1 << 28
+    for s in range(0, n, step):                               # exact round trip, compared on the GPU
+        e = min(n, s + step)
+        assert torch.equal(y[s:e].view(torch.int32), x[s:e].view(torch.int32)), s
+    for c0, count in ((0, 8), ((1 << 19) - 4, 8), (chunks - 8, 8)):   # chunk 2^19 starts at value 2^32
+        print("large lossless, chunks from", c0, flush=True)
+        xs = _host(x[c0 * C:min(n, (c0 + count) * C)])
+        want = zl_ref.compress(xs)
+        wt = want[32:32 + 8 * count].view(np.uint64) & np.uint64((1 << 62) - 1)
+        start = int(ends[c0 - 1]) if c0 else 0
+        assert np.array_equal(_host(ends[c0:c0 + count]) - start, wt.astype(np.int64)), c0
+        p0 = 32 + 8 * chunks + start
+        assert np.array_equal(_host(c[p0:p0 + int(wt[-1])]), want[32 + 8 * count:]), c0
+    del x, c, y
+    torch.cuda.empty_cache()
