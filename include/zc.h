@@ -64,6 +64,12 @@ enum zc_class {
   ZC_OPT_STATE = 4      /* ZeRO-1 reduce-scatter / optimizer-state traffic */
 };
 
+/* The two hybrid schemes: fixed-rate codec everywhere at two rates (Sec. III-B, Table
+ * III), or lossless codec for model-parallel and ZeRO traffic and the fixed-rate codec for
+ * data-parallel gradients (Sec. III-A, Table II). */
+enum zc_scheme { ZC_SCHEME_ZHYBRID = 0, ZC_SCHEME_MZHYBRID = 1 };
+enum zc_codec { ZC_CODEC_FIXED_RATE = 0, ZC_CODEC_LOSSLESS = 1 };
+
 /* Library version, major*100 + minor. */
 int zc_version(void);
 
@@ -77,6 +83,13 @@ int zc_rate_supported(int rate);
  * data-parallel gradients (8, as in Sec. IV-F), high rate (16) for everything
  * else.  Returns 0 for an unknown class. */
 int zc_rate_for_class(enum zc_class c);
+
+/* Codec for a message class under a scheme: ZC_CODEC_FIXED_RATE (the zc_* and zc2d_*
+ * calls) with its rate in *rate, or ZC_CODEC_LOSSLESS (the zl_* calls) with *rate = 0.
+ * ZHybrid: the rates of zc_rate_for_class.  MZHybrid: lossless for every class except
+ * data-parallel gradients, which keep the low rate (8; Sec. IV-E also ran 16).  Returns -1
+ * for an unknown scheme or class.  `rate` is a host pointer and may be NULL. */
+int zc_codec_for_class(enum zc_scheme s, enum zc_class c, int* rate);
 
 /* Bytes of the compressed form of n values: ceil(n/4) * rate/2, which is
  * n*rate/8 when 4 divides n.  0 if the rate is unsupported. */

@@ -560,6 +560,14 @@ int zc_rate_for_class(enum zc_class c) {
   }
 }
 
+int zc_codec_for_class(enum zc_scheme s, enum zc_class c, int* rate) {
+  const int fixed = zc_rate_for_class(c);
+  if (fixed == 0 || (s != ZC_SCHEME_ZHYBRID && s != ZC_SCHEME_MZHYBRID)) return -1;
+  const bool lossless = s == ZC_SCHEME_MZHYBRID && c != ZC_DP_GRADIENT;
+  if (rate) *rate = lossless ? 0 : fixed;
+  return lossless ? ZC_CODEC_LOSSLESS : ZC_CODEC_FIXED_RATE;
+}
+
 size_t zc_compressed_size(size_t n, int rate) {
   if (!zc_rate_supported(rate)) return 0;
   return (n / 4 + (n % 4 ? 1 : 0)) * (size_t)(rate / 2);

@@ -17,8 +17,10 @@ ZC_ERR_NULL, ZC_ERR_RATE, ZC_ERR_SIZE, ZC_ERR_CAPACITY = -1, -2, -3, -4
 ZC_ERR_K, ZC_ERR_ALIGN, ZC_ERR_LAUNCH, ZC_ERR_DTYPE, ZC_ERR_STREAM = -5, -6, -7, -8, -9
 ZC_F32, ZC_BF16, ZC_F16 = 0, 1, 2
 ZC_DP_GRADIENT, ZC_TP_ACTIVATION, ZC_PP_ACTIVATION, ZC_ZERO_PARAM, ZC_OPT_STATE = range(5)
+ZC_SCHEME_ZHYBRID, ZC_SCHEME_MZHYBRID = 0, 1
+ZC_CODEC_FIXED_RATE, ZC_CODEC_LOSSLESS = 0, 1
 
-EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_compressed_size",
+EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class", "zc_codec_for_class", "zc_compressed_size",
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
            "zc_compress_half", "zc_decompress_half",
            "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress", "zc2d_reduce_compressed",
@@ -49,6 +51,7 @@ def lib():
         L.zc_strerror.argtypes = [ctypes.c_int]
         L.zc_rate_supported.argtypes = [ctypes.c_int]
         L.zc_rate_for_class.argtypes = [ctypes.c_int]
+        L.zc_codec_for_class.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         L.zc_compressed_size.restype = ctypes.c_size_t
         L.zc_compressed_size.argtypes = [ctypes.c_size_t, ctypes.c_int]
         L.zc_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
@@ -99,6 +102,15 @@ def zc_rate_supported(rate):
 
 def zc_rate_for_class(message_class):
     return int(lib().zc_rate_for_class(int(message_class)))
+
+
+def zc_codec_for_class(scheme, message_class):
+    """(codec, rate) for a message class under a scheme; raises for unknown ones."""
+    rate = ctypes.c_int(0)
+    codec = int(lib().zc_codec_for_class(int(scheme), int(message_class), ctypes.byref(rate)))
+    if codec < 0:
+        raise ValueError("unknown scheme or message class")
+    return codec, int(rate.value)
 
 
 def zc_compressed_size(n, rate):

@@ -37,6 +37,17 @@ def test_sizes_and_policy():
     for c in (zc.ZC_TP_ACTIVATION, zc.ZC_PP_ACTIVATION, zc.ZC_ZERO_PARAM, zc.ZC_OPT_STATE):
         assert zc.zc_rate_for_class(c) == 16
     assert zc.zc_rate_for_class(99) == 0
+    # the two hybrid schemes (Table II, Table III)
+    others = (zc.ZC_TP_ACTIVATION, zc.ZC_PP_ACTIVATION, zc.ZC_ZERO_PARAM, zc.ZC_OPT_STATE)
+    assert zc.zc_codec_for_class(zc.ZC_SCHEME_ZHYBRID, zc.ZC_DP_GRADIENT) == (zc.ZC_CODEC_FIXED_RATE, 8)
+    assert zc.zc_codec_for_class(zc.ZC_SCHEME_MZHYBRID, zc.ZC_DP_GRADIENT) == (zc.ZC_CODEC_FIXED_RATE, 8)
+    for c in others:
+        assert zc.zc_codec_for_class(zc.ZC_SCHEME_ZHYBRID, c) == (zc.ZC_CODEC_FIXED_RATE, 16)
+        assert zc.zc_codec_for_class(zc.ZC_SCHEME_MZHYBRID, c) == (zc.ZC_CODEC_LOSSLESS, 0)
+    for bad in ((2, 0), (0, 9), (-1, 0)):
+        with pytest.raises(ValueError):
+            zc.zc_codec_for_class(*bad)
+    assert zc.lib().zc_codec_for_class(1, 1, None) == zc.ZC_CODEC_LOSSLESS      # the rate pointer may be NULL
 
 
 def test_error_strings():
