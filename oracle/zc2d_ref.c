@@ -43,6 +43,8 @@
 #define ZC2D_COEFFS 16
 
 /* pinned 1-D building blocks from zc_ref.c */
+float zc_ref_widen(uint16_t h, int dtype);
+uint16_t zc_ref_narrow(float f, int dtype);
 void zc_ref_fwd_lift(int32_t v[4]);
 void zc_ref_inv_lift(int32_t v[4]);
 uint32_t zc_ref_negabinary(int32_t c);
@@ -273,6 +275,53 @@ int zc2d_ref_reduce_compressed(const void *const *in, int k, size_t rows, size_t
       for (size_t r = 0; r < 4; ++r)
         for (size_t q = 0; q < 4; ++q) f[4 * r + q] = s[4 * (r < rv ? r : rv - 1) + (q < cv ? q : cv - 1)];
       zc2d_ref_encode_block(f, rate, (uint8_t *)out + at);
+    }
+  return ZC2D_OK;
+}
+
+/* ---- half-precision matrices ----------------------------------------------------------
+ * bf16 / fp16 matrices (dtype codes as in zc_ref.c: 1 = bf16, 2 = fp16; the paper does not
+ * state its message precision): every value is widened to fp32, which is exact, and the
+ * matrix is then compressed as an fp32 matrix; decompression rounds each fp32 value to the
+ * nearest half-precision value, ties to even.  The stream is the ordinary ZC-2D stream. */
+
+int zc2d_ref_compress_half(const uint16_t *in, int dtype, size_t rows, size_t cols, int rate, void *out, size_t out_cap) {
+  if (dtype != 1 && dtype != 2) return -8;
+  if (!zc2d_ref_rate_supported(rate)) return ZC2D_ERR_RATE;
+  if (rows == 0 || cols == 0) return ZC2D_OK;
+  if (!in || !out) return ZC2D_ERR_NULL;
+  if (out_cap < zc2d_ref_compressed_size(rows, cols, rate)) return ZC2D_ERR_CAPACITY;
+  size_t bc = (cols + 3) / 4, br = (rows + 3) / 4;
+  for (size_t bi = 0; bi < br; ++bi)
+    for (size_t bj = 0; bj < bc; ++bj) {
+      float x[16];
+      for (int r = 0; r < 4; ++r)
+        for (int c = 0; c < 4; ++c) {
+          size_t rr = 4 * bi + (size_t)r, cc = 4 * bj + (size_t)c;
+          if (rr >= rows) rr = rows - 1;
+          if (cc >= cols) cc = cols - 1;
+          x[4 * r + c] = zc_ref_widen(in[rr * cols + cc], dtype);
+        }
+      zc2d_ref_encode_block(x, rate, (uint8_t *)out + (bi * bc + bj) * (size_t)(2 * rate));
+    }
+  return ZC2D_OK;
+}
+
+int zc2d_ref_decompress_half(const void *in, size_t rows, size_t cols, int rate, int dtype, uint16_t *out) {
+  if (dtype != 1 && dtype != 2) return -8;
+  if (!zc2d_ref_rate_supported(rate)) return ZC2D_ERR_RATE;
+  if (rows == 0 || cols == 0) return ZC2D_OK;
+  if (!in || !out) return ZC2D_ERR_NULL;
+  size_t bc = (cols + 3) / 4, br = (rows + 3) / 4;
+  for (size_t bi = 0; bi < br; ++bi)
+    for (size_t bj = 0; bj < bc; ++bj) {
+      float x[16];
+      zc2d_ref_decode_block((const uint8_t *)in + (bi * bc + bj) * (size_t)(2 * rate), rate, x);
+      for (int r = 0; r < 4; ++r)
+        for (int c = 0; c < 4; ++c) {
+          size_t rr = 4 * bi + (size_t)r, cc = 4 * bj + (size_t)c;
+          if (rr < rows && cc < cols) out[rr * cols + cc] = zc_ref_narrow(x[4 * r + c], dtype);
+        }
     }
   return ZC2D_OK;
 }

@@ -38,6 +38,10 @@ def lib():
                                           ctypes.c_void_p]
         L.zc2d_ref_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t,
                                                  ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+        L.zc2d_ref_compress_half.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
+                                             ctypes.c_void_p, ctypes.c_size_t]
+        L.zc2d_ref_decompress_half.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_void_p]
         _ready = True
     return L
 
@@ -132,4 +136,29 @@ def reduce_compressed(streams, rows, cols, rate):
     rc = lib().zc2d_ref_reduce_compressed(ptrs, k, int(rows), int(cols), int(rate), out.ctypes.data, out.size)
     if rc != 0:
         raise ValueError("zc2d_ref_reduce_compressed failed: %d" % rc)
+    return out
+
+
+BF16, F16 = 1, 2
+
+
+def compress_half(bits, dtype, rate):
+    """bits: 2-D uint16 array of bf16 / fp16 bit patterns."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    rows, cols = b.shape
+    out = np.zeros(compressed_size(rows, cols, rate), dtype=np.uint8)
+    rc = lib().zc2d_ref_compress_half(b.ctypes.data, int(dtype), rows, cols, int(rate), out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError("zc2d_ref_compress_half failed: %d" % rc)
+    return out
+
+
+def decompress_half(stream, rows, cols, rate, dtype):
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    if s.size < compressed_size(rows, cols, rate):
+        raise ValueError("stream too short")
+    out = np.zeros((rows, cols), dtype=np.uint16)
+    rc = lib().zc2d_ref_decompress_half(s.ctypes.data, int(rows), int(cols), int(rate), int(dtype), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("zc2d_ref_decompress_half failed: %d" % rc)
     return out

@@ -239,3 +239,30 @@ def test_reduce_edge_fill_comes_from_the_sum(o2):
     assert np.allclose(full[:2, :2], a + b, rtol=1e-3)
     assert np.allclose(full[2:, :2], np.broadcast_to((a + b)[1], (2, 2)), rtol=1e-3)      # last row repeated
     assert np.allclose(full[:2, 2:], np.broadcast_to((a + b)[:, 1:], (2, 2)), rtol=1e-3)  # last column repeated
+
+
+@pytest.mark.parametrize("name", ["bf16", "f16"])
+def test_half_precision_matrices_are_compositions(o2, oracle, name):
+    """Widening (pinned against numpy in the 1-D tests) then the fp32 codec; the fp32 decoder then
+    narrowing with numpy's own round-to-nearest-even cast (fp16) or the closed form on bits (bf16)."""
+    from paper_2409_02423_amd import workloads
+    rows, cols = 37, 54
+    f = (workloads.activation_gelu(rows * cols, config=3, index=4) * np.float32(2.5)).reshape(rows, cols)
+    if name == "f16":
+        bits, code = f.astype(np.float16).view(np.uint16), o2.F16
+        wide = bits.view(np.float16).astype(np.float32)
+    else:
+        bits, code = (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16), o2.BF16
+        wide = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    for rate in (2, 4, 8, 16):
+        s = o2.compress_half(bits, code, rate)
+        assert np.array_equal(s, o2.compress(wide, rate)), (name, rate)
+        d = o2.decompress(s, rows, cols, rate)
+        if name == "f16":
+            want = d.astype(np.float16).view(np.uint16)
+        else:
+            u = d.view(np.uint32).astype(np.uint64)
+            want = ((u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)).astype(np.uint16)
+        assert np.array_equal(o2.decompress_half(s, rows, cols, rate, code), want), (name, rate)
+    with pytest.raises(ValueError):
+        o2.compress_half(bits, 0, 4)
