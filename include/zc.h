@@ -179,6 +179,18 @@ int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d
  * must not overlap d_in. */
 int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream);
 
+/* Half-precision matrices (bf16 / fp16, 2 bytes per value; the usual precision of
+ * [tokens x hidden] activations): every value is widened to fp32, which is exact, and the
+ * matrix is compressed exactly as zc2d_compress would; the stream is an ordinary ZC-2D
+ * stream.  dtype is ZC_BF16 or ZC_F16 (else ZC_ERR_DTYPE). */
+int zc2d_compress_half(const void* d_in, int dtype, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap,
+                       void* stream);
+
+/* Decompress to a half-precision matrix: what zc2d_decompress would produce, each value
+ * rounded to the nearest bf16 / fp16 (ties to even; magnitudes beyond the largest finite
+ * value become infinity). */
+int zc2d_decompress_half(const void* d_in, size_t rows, size_t cols, int rate, int dtype, void* d_out, void* stream);
+
 /* The reduce-scatter step (Sec. IV-A) on matrix-shaped messages: d_in is a HOST array of
  * k device pointers (k in [1, 16]) to compressed matrices of the same shape and rate.
  * Writes to d_out the compressed form of the element-wise fp32 sum ((x_0 + x_1) + x_2) +

@@ -12,6 +12,7 @@
 
 #include "../../include/zc.h"
 #include "zc2d_codec.h"
+#include "zc_half.h"
 
 namespace {
 
@@ -72,16 +73,23 @@ struct Cursor {
 };
 
 // The block under the cursor as fp32 bit patterns; parts that stick out of the matrix
-// repeat the last valid row / column.
-__device__ __forceinline__ void load_block(const float* in, const Walk& w, const Cursor& c, uint32_t (&x)[16]) {
+// repeat the last valid row / column.  DT: the matrix holds fp32, or bf16 / fp16 values
+// that are widened (exactly) on the way in.
+template <int DT>
+__device__ __forceinline__ void load_block(const void* in, const Walk& w, const Cursor& c, uint32_t (&x)[16]) {
   if (c.whole(w)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + c.first + r * w.cols));
-      x[4 * r] = v.x; x[4 * r + 1] = v.y; x[4 * r + 2] = v.z; x[4 * r + 3] = v.w;
+      if constexpr (DT == kF32) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const float*>(in) + c.first + r * w.cols));
+        x[4 * r] = v.x; x[4 * r + 1] = v.y; x[4 * r + 2] = v.z; x[4 * r + 3] = v.w;
+      } else {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(in) + c.first + r * w.cols));
+        x[4 * r] = widen_half<DT>(v.x & 0xFFFFu); x[4 * r + 1] = widen_half<DT>(v.x >> 16);
+        x[4 * r + 2] = widen_half<DT>(v.y & 0xFFFFu); x[4 * r + 3] = widen_half<DT>(v.y >> 16);
+      }
     }
   } else {
-    const uint32_t* bits = reinterpret_cast<const uint32_t*>(in);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -89,18 +97,27 @@ __device__ __forceinline__ void load_block(const float* in, const Walk& w, const
         size_t rr = 4 * c.bi + r, cc = 4 * c.bj + q;
         rr = rr < w.rows ? rr : w.rows - 1;
         cc = cc < w.cols ? cc : w.cols - 1;
-        x[4 * r + q] = bits[rr * w.cols + cc];
+        if constexpr (DT == kF32) x[4 * r + q] = static_cast<const uint32_t*>(in)[rr * w.cols + cc];
+        else x[4 * r + q] = widen_half<DT>(static_cast<const uint16_t*>(in)[rr * w.cols + cc]);
       }
   }
 }
 
-__device__ __forceinline__ void store_block(float* out, const Walk& w, const Cursor& c, const float (&y)[16]) {
+// The reverse; half-precision values are rounded to nearest, ties to even.
+template <int DT>
+__device__ __forceinline__ void store_block(void* out, const Walk& w, const Cursor& c, const float (&y)[16]) {
   if (c.whole(w)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const u32x4 v = {__float_as_uint(y[4 * r]), __float_as_uint(y[4 * r + 1]), __float_as_uint(y[4 * r + 2]),
-                       __float_as_uint(y[4 * r + 3])};
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + c.first + r * w.cols));
+      if constexpr (DT == kF32) {
+        const u32x4 v = {__float_as_uint(y[4 * r]), __float_as_uint(y[4 * r + 1]), __float_as_uint(y[4 * r + 2]),
+                         __float_as_uint(y[4 * r + 3])};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<float*>(out) + c.first + r * w.cols));
+      } else {
+        const u32x2 v = {narrow_half<DT>(y[4 * r]) | narrow_half<DT>(y[4 * r + 1]) << 16,
+                         narrow_half<DT>(y[4 * r + 2]) | narrow_half<DT>(y[4 * r + 3]) << 16};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(out) + c.first + r * w.cols));
+      }
     }
   } else {
 #pragma unroll
@@ -108,7 +125,10 @@ __device__ __forceinline__ void store_block(float* out, const Walk& w, const Cur
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const size_t rr = 4 * c.bi + r, cc = 4 * c.bj + q;
-        if (rr < w.rows && cc < w.cols) out[rr * w.cols + cc] = y[4 * r + q];
+        if (rr < w.rows && cc < w.cols) {
+          if constexpr (DT == kF32) static_cast<float*>(out)[rr * w.cols + cc] = y[4 * r + q];
+          else static_cast<uint16_t*>(out)[rr * w.cols + cc] = (uint16_t)narrow_half<DT>(y[4 * r + q]);
+        }
       }
   }
 }
@@ -145,8 +165,8 @@ __device__ __forceinline__ void store_words(uint8_t* p, const uint32_t (&W)[NW])
   }
 }
 
-template <int RATE>
-__global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __restrict__ in, Walk w,
+template <int RATE, int DT>
+__global__ __launch_bounds__(kThreads) void compress2d_kernel(const void* __restrict__ in, Walk w,
                                                               uint8_t* __restrict__ out) {
   __shared__ __attribute__((aligned(16))) uint32_t expand[256];
   stage_table<256>(g_expand.v, expand);
@@ -156,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __res
   Cursor cur;
   cur.start(w, b0);
   uint32_t x[16];
-  load_block(in, w, cur, x);
+  load_block<DT>(in, w, cur, x);
   // The first block has to have arrived before the loop starts: with loads still in flight
   // at its entry, every pass would wait for its own prefetch as well (loads return in order).
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -167,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __res
     next.advance(w);
     const bool more = next.b < w.blocks;
     uint32_t xn[16], W[NW];
-    if (more) load_block(in, w, next, xn);
+    if (more) load_block<DT>(in, w, next, xn);
     zc2d::encode_block<RATE>(x, expand, W, AnyLane());
     store_words<NW>(out + cur.b * zc2d::Traits<RATE>::kBlockBytes, W);
     if (!more) break;
@@ -177,9 +197,9 @@ __global__ __launch_bounds__(kThreads) void compress2d_kernel(const float* __res
   }
 }
 
-template <int RATE>
+template <int RATE, int DT>
 __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* __restrict__ in, Walk w,
-                                                                float* __restrict__ out) {
+                                                                void* __restrict__ out) {
   __shared__ __attribute__((aligned(16))) uint32_t token[1 << zc2d::kLookahead];
   stage_table<(1 << zc2d::kLookahead)>(g_token.v, token);
   constexpr int NW = zc2d::Traits<RATE>::kWords;
@@ -199,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* _
     load_words<NW>(in + next.b * zc2d::Traits<RATE>::kBlockBytes, Wn);   // the next block's stream, ahead of time
     float y[16];
     zc2d::decode_block<RATE>(W, token, y, AnyLane());
-    store_block(out, w, cur, y);
+    store_block<DT>(out, w, cur, y);
     if (!more) break;
 #pragma unroll
     for (int i = 0; i < NW; ++i) W[i] = Wn[i];
@@ -326,16 +346,10 @@ constexpr size_t kMaxValues = (size_t)1 << 40;
     default: return ZC_ERR_RATE;       \
   }
 
-extern "C" {
+namespace {
 
-int zc2d_rate_supported(int rate) { return rate == 2 || rate == 4 || rate == 8 || rate == 16; }
-
-size_t zc2d_compressed_size(size_t rows, size_t cols, int rate) {
-  if (!zc2d_rate_supported(rate)) return 0;
-  return ((rows + 3) / 4) * ((cols + 3) / 4) * (size_t)(2 * rate);
-}
-
-int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap, void* stream) {
+template <int DT>
+int launch_compress2d(const void* d_in, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap, void* stream) {
   if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
   if (rows == 0 || cols == 0) return ZC_OK;
   if (!d_in || !d_out) return ZC_ERR_NULL;
@@ -346,13 +360,14 @@ int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned grid = grid_for(blocks);
   const Walk w = walk_for(rows, cols, grid);
-#define CALL(R) hipLaunchKernelGGL(compress2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, d_in, w, static_cast<uint8_t*>(d_out))
+#define CALL(R) hipLaunchKernelGGL((compress2d_kernel<R, DT>), dim3(grid), dim3(kThreads), 0, s, d_in, w, static_cast<uint8_t*>(d_out))
   ZC2D_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
 }
 
-int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream) {
+template <int DT>
+int launch_decompress2d(const void* d_in, size_t rows, size_t cols, int rate, void* d_out, void* stream) {
   if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
   if (rows == 0 || cols == 0) return ZC_OK;
   if (!d_in || !d_out) return ZC_ERR_NULL;
@@ -362,10 +377,42 @@ int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float*
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned grid = grid_for(blocks);
   const Walk w = walk_for(rows, cols, grid);
-#define CALL(R) hipLaunchKernelGGL(decompress2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), w, d_out)
+#define CALL(R) hipLaunchKernelGGL((decompress2d_kernel<R, DT>), dim3(grid), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), w, d_out)
   ZC2D_DISPATCH_RATE(rate, CALL)
 #undef CALL
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int zc2d_rate_supported(int rate) { return rate == 2 || rate == 4 || rate == 8 || rate == 16; }
+
+size_t zc2d_compressed_size(size_t rows, size_t cols, int rate) {
+  if (!zc2d_rate_supported(rate)) return 0;
+  return ((rows + 3) / 4) * ((cols + 3) / 4) * (size_t)(2 * rate);
+}
+
+int zc2d_compress(const float* d_in, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap, void* stream) {
+  return launch_compress2d<kF32>(d_in, rows, cols, rate, d_out, out_cap, stream);
+}
+
+int zc2d_decompress(const void* d_in, size_t rows, size_t cols, int rate, float* d_out, void* stream) {
+  return launch_decompress2d<kF32>(d_in, rows, cols, rate, d_out, stream);
+}
+
+int zc2d_compress_half(const void* d_in, int dtype, size_t rows, size_t cols, int rate, void* d_out, size_t out_cap,
+                       void* stream) {
+  if (dtype == ZC_BF16) return launch_compress2d<kBF16>(d_in, rows, cols, rate, d_out, out_cap, stream);
+  if (dtype == ZC_F16) return launch_compress2d<kF16>(d_in, rows, cols, rate, d_out, out_cap, stream);
+  return ZC_ERR_DTYPE;
+}
+
+int zc2d_decompress_half(const void* d_in, size_t rows, size_t cols, int rate, int dtype, void* d_out, void* stream) {
+  if (dtype == ZC_BF16) return launch_decompress2d<kBF16>(d_in, rows, cols, rate, d_out, stream);
+  if (dtype == ZC_F16) return launch_decompress2d<kF16>(d_in, rows, cols, rate, d_out, stream);
+  return ZC_ERR_DTYPE;
 }
 
 int zc2d_reduce_compressed(const void* const* d_in, int k, size_t rows, size_t cols, int rate, void* d_out,

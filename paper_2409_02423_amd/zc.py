@@ -24,6 +24,7 @@ EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class"
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
            "zc_compress_half", "zc_decompress_half",
            "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress", "zc2d_reduce_compressed",
+           "zc2d_compress_half", "zc2d_decompress_half",
            "zl_max_compressed_size", "zl_compress", "zl_stream_bytes", "zl_decompress", "zl_compress16", "zl_decompress16")
 
 _lib = None
@@ -75,6 +76,10 @@ def lib():
                                     ctypes.c_size_t, ctypes.c_void_p]
         L.zc2d_decompress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p]
+        L.zc2d_compress_half.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.zc2d_decompress_half.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_void_p, ctypes.c_void_p]
         L.zc2d_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                              ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.zl_max_compressed_size.restype = ctypes.c_size_t
@@ -331,6 +336,47 @@ def zc2d_decompress(d_in, rows, cols, rate, d_out=None, stream=None):
                                _stream_handle(stream))
     if rc != ZC_OK:
         raise ZcError(rc, "zc2d_decompress")
+    return d_out
+
+
+def zc2d_compress_half(d_in, rate, d_out=None, stream=None):
+    """2-D bfloat16 / float16 CUDA tensor -> uint8 CUDA tensor in format ZC-2D."""
+    dtype = _half_dtype(d_in)
+    _check_device_tensor(d_in, d_in.dtype, "d_in")
+    if d_in.dim() != 2:
+        raise TypeError("d_in must be a matrix")
+    rows, cols = d_in.shape
+    if d_out is None:
+        size = zc2d_compressed_size(rows, cols, rate)
+        if size == 0 and rows * cols != 0:
+            raise ZcError(ZC_ERR_RATE, "zc2d_compressed_size")
+        d_out = torch.empty(size, dtype=torch.uint8, device=d_in.device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zc2d_compress_half(d_in.data_ptr(), dtype, rows, cols, int(rate), d_out.data_ptr(), d_out.numel(),
+                                  _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_compress_half")
+    return d_out
+
+
+def zc2d_decompress_half(d_in, rows, cols, rate, dtype=None, d_out=None, stream=None):
+    """Stream in format ZC-2D -> bfloat16 / float16 CUDA tensor of shape (rows, cols); give torch dtype or d_out."""
+    _check_device_tensor(d_in, torch.uint8, "d_in")
+    need = zc2d_compressed_size(rows, cols, rate)
+    if need == 0 and rows * cols != 0:
+        raise ZcError(ZC_ERR_RATE, "zc2d_decompress_half")
+    if d_in.numel() < need:
+        raise ValueError("d_in holds %d bytes, need %d" % (d_in.numel(), need))
+    if d_out is None:
+        d_out = torch.empty((rows, cols), dtype=dtype, device=d_in.device)
+    code = _half_dtype(d_out)
+    _check_device_tensor(d_out, d_out.dtype, "d_out")
+    if d_out.numel() < rows * cols:
+        raise ValueError("d_out holds %d values, need %d" % (d_out.numel(), rows * cols))
+    rc = lib().zc2d_decompress_half(d_in.data_ptr(), int(rows), int(cols), int(rate), code, d_out.data_ptr(),
+                                    _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_decompress_half")
     return d_out
 
 

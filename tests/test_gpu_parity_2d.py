@@ -195,6 +195,30 @@ def test_reduce_matches_reference(gpu, ref, rate):
         _same_bytes(_host(acc), ref.reduce_compressed(comp[:2], rows, cols, rate), rate, "reduce in place")
 
 
+@pytest.mark.parametrize("name", ["bf16", "f16"])
+def test_half_precision_matrices(gpu, ref, name):
+    import torch
+    for rows, cols in ((64, 256), (37, 54), (5, 1028), (1026, 6)):
+        f = (workloads.activation_gelu(rows * cols, config=3, index=rows) * np.float32(2.5)).reshape(rows, cols)
+        if name == "f16":
+            bits, code, tdt = f.astype(np.float16).view(np.uint16), ref.F16, torch.float16
+        else:
+            bits, code, tdt = (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16), ref.BF16, torch.bfloat16
+        dbits = _dev(bits.view(np.int16)).view(tdt)
+        for rate in RATES:
+            print("2d", name, "shape", rows, cols, "rate", rate, flush=True)
+            want = ref.compress_half(bits, code, rate)
+            got = gpu.zc2d_compress_half(dbits, rate)
+            _same_bytes(_host(got), want, rate, "%s compress %dx%d r%d" % (name, rows, cols, rate))
+            back = gpu.zc2d_decompress_half(got, rows, cols, rate, dtype=tdt)
+            wantd = ref.decompress_half(want, rows, cols, rate, code)
+            assert np.array_equal(_host(back.view(torch.int16)).view(np.uint16), wantd), (name, rows, cols, rate)
+    with pytest.raises(TypeError):
+        gpu.zc2d_compress_half(torch.zeros((4, 4), device="cuda"), 4)
+    assert gpu.lib().zc2d_compress_half(0x10000, 0, 4, 4, 4, 0x10000, 100, None) == gpu.ZC_ERR_DTYPE
+    assert gpu.lib().zc2d_decompress_half(0x10000, 4, 4, 4, 7, 0x10000, None) == gpu.ZC_ERR_DTYPE
+
+
 def test_reduce_errors(gpu):
     import torch
     c = torch.zeros(gpu.zc2d_compressed_size(8, 8, 4), dtype=torch.uint8, device="cuda")
