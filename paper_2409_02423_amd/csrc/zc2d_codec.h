@@ -21,10 +21,10 @@
 //     token starts one bit after the previous one ended, so the code is the pattern
 //     with each one moved up by its rank (two look-ups in a 256-entry table) plus that
 //     word shifted by one;
-//   * decoder: a table indexed by the next 10 stream bits decodes all the tokens that
-//     lie whole within them; it is used when its result stays inside the budget and
-//     below the last coefficient (whose token has no closing one), otherwise one token
-//     is decoded by count-trailing-zeros with the limits applied.  A budget cut inside
+//   * decoder: a table indexed by the next 9 stream bits and by how far the last
+//     coefficient is (whose token has no closing one) decodes all the tokens that lie
+//     whole within those bits; it is used when its result stays inside the budget,
+//     otherwise one token is decoded by count-trailing-zeros with the limits applied.  A budget cut inside
 //     a run places the decoded one after the zeros read so far, which is the lowest
 //     index still possible.
 #ifndef ZC2D_CODEC_H
@@ -101,28 +101,41 @@ constexpr ExpandTable build_expand_table() {
   return t;
 }
 
-// Decoder: entry for the next kLookahead stream bits at the start of a group test, with
-// all the tokens (one, zeros, one) that lie whole within them and a closing zero if it
-// follows: bits 0..9 the ones, as positions past the current coefficient; bits 12..15
-// how many coefficients were passed; bits 16..19 how many stream bits were used; bit 20
-// set if the closing zero was among them.
-constexpr int kLookahead = 10;
-struct TokenTable { uint32_t v[1 << kLookahead]; };
+// Decoder: entry for the next kLookahead stream bits at the start of a group test, when
+// `room` coefficients lie between the current one and the last (rows room = 0 ..
+// kLookahead-1, and one row for everything above, where the end cannot be reached within
+// the look-ahead).  It holds all the tokens that lie whole within those bits: group bit,
+// zeros, closing one; a run of `room` zeros reaches the last coefficient, whose one needs
+// no closing bit and after which the plane is done; a group bit 0 closes the plane.
+// Bits 0..9: the ones, as positions past the current coefficient; bits 12..15: how many
+// coefficients were passed; bits 16..19: how many stream bits were used (0: the first
+// token does not end within the look-ahead); bit 20: the plane is done.
+constexpr int kLookahead = 9;
+constexpr int kTokenRows = kLookahead + 1;
+struct TokenTable { uint32_t v[kTokenRows << kLookahead]; };
 constexpr TokenTable build_token_table() {
   TokenTable t{};
-  for (uint32_t s = 0; s < (1u << kLookahead); ++s) {
-    uint32_t ones = 0, passed = 0, used = 0, closed = 0;
-    while (used < (uint32_t)kLookahead) {
-      if (((s >> used) & 1u) == 0u) { closed = 1; ++used; break; }
-      uint32_t z = 0;
-      while (used + 1 + z < (uint32_t)kLookahead && ((s >> (used + 1 + z)) & 1u) == 0u) ++z;
-      if (used + 1 + z >= (uint32_t)kLookahead) break;   // the closing one is out of sight
-      ones |= 1u << (passed + z);
-      passed += z + 1;
-      used += z + 2;
+  for (uint32_t room = 0; room < (uint32_t)kTokenRows; ++room)
+    for (uint32_t s = 0; s < (1u << kLookahead); ++s) {
+      uint32_t ones = 0, passed = 0, used = 0, done = 0;
+      for (;;) {
+        if (passed > room) { done = 1; break; }             // the last coefficient has been dealt with
+        if (used >= (uint32_t)kLookahead) break;
+        if (((s >> used) & 1u) == 0u) { done = 1; ++used; break; }
+        uint32_t z = 0;
+        bool in_sight = true;
+        while (passed + z < room) {
+          if (used + 1 + z >= (uint32_t)kLookahead) { in_sight = false; break; }
+          if ((s >> (used + 1 + z)) & 1u) break;
+          ++z;
+        }
+        if (!in_sight) break;
+        ones |= 1u << (passed + z);
+        used += 1 + z + (passed + z == room ? 0 : 1);       // no closing one at the last coefficient
+        passed += z + 1;
+      }
+      t.v[(room << kLookahead) + s] = ones | passed << 12 | used << 16 | done << 20;
     }
-    t.v[s] = ones | passed << 12 | used << 16 | closed << 20;
-  }
   return t;
 }
 
@@ -268,10 +281,10 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
     const bool active = watch < 16u && left > 0u;
     if (!any_lane_active(active)) break;
     if (active) {
-      // all the tokens that lie whole in the next bits, if the limits cannot matter to them
-      const uint32_t e = token[W[0] & ((1u << kLookahead) - 1u)];
+      // all the tokens that lie whole in the next bits, if the budget covers them
+      const uint32_t e = token[(umin(15u - i, (uint32_t)kLookahead) << kLookahead) + (W[0] & ((1u << kLookahead) - 1u))];
       const uint32_t t_used = (e >> 16) & 15u, t_passed = (e >> 12) & 15u;
-      const bool fast = t_used != 0u && t_used <= left && i + t_passed <= 15u;
+      const bool fast = t_used != 0u && t_used <= left;
       // otherwise one token with the limits applied (its group bit is a one, or the table
       // would have served): zeros up to the one; the run ends at the last coefficient or
       // at the budget

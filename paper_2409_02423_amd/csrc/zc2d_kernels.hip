@@ -4,7 +4,7 @@
 // stride, so that the 64 lanes of a wavefront read four contiguous 1 KiB spans (one per
 // matrix row of the block row) and write one contiguous span of 64 * 2*RATE stream bytes.
 // A block lives in registers from load to store; LDS holds only the coder's look-up table
-// (1 KiB for the encoder, 4 KiB for the decoder).  No matrix cores: nothing here is a
+// (1 KiB for the encoder, 20 KiB for the decoder).  No matrix cores: nothing here is a
 // contraction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -200,8 +200,8 @@ __global__ __launch_bounds__(kThreads) void compress2d_kernel(const void* __rest
 template <int RATE, int DT>
 __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* __restrict__ in, Walk w,
                                                                 void* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) uint32_t token[1 << zc2d::kLookahead];
-  stage_table<(1 << zc2d::kLookahead)>(g_token.v, token);
+  __shared__ __attribute__((aligned(16))) uint32_t token[zc2d::kTokenRows << zc2d::kLookahead];
+  stage_table<(zc2d::kTokenRows << zc2d::kLookahead)>(g_token.v, token);
   constexpr int NW = zc2d::Traits<RATE>::kWords;
   const size_t b0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
   if (b0 >= w.blocks) return;
@@ -237,10 +237,10 @@ struct ChunkPointers2d {
 template <int RATE>
 __global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chunks, int k, Walk w, uint8_t* out) {
   __shared__ __attribute__((aligned(16))) uint32_t expand[256];
-  __shared__ __attribute__((aligned(16))) uint32_t token[1 << zc2d::kLookahead];
+  __shared__ __attribute__((aligned(16))) uint32_t token[zc2d::kTokenRows << zc2d::kLookahead];
   for (int i = threadIdx.x; i < 256 / 4; i += kThreads)
     reinterpret_cast<uint4*>(expand)[i] = reinterpret_cast<const uint4*>(g_expand.v)[i];
-  stage_table<(1 << zc2d::kLookahead)>(g_token.v, token);   // (its barrier covers both tables)
+  stage_table<(zc2d::kTokenRows << zc2d::kLookahead)>(g_token.v, token);   // (its barrier covers both tables)
   constexpr int NW = zc2d::Traits<RATE>::kWords;
   const size_t b0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
   if (b0 >= w.blocks) return;
