@@ -28,8 +28,11 @@ INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one
 # HBM bytes per launch (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, the scale a 1 GiB
 # device copy gives on this machine) and wave-level VALU instructions per launch
 # (SQ_INSTS_VALU; x 64 lanes = lane operations).
-MEASURED_TRAFFIC_BYTES = {"compress": 1216294233, "decompress": 1208248851, "reduce": 402916751}
-MEASURED_VALU_WAVE_INSTS = {"compress": 61128704, "decompress": 13762560, "reduce": 86425600}
+# the kernels behind the three calls of the step at rate 4 (names as rocprofv3 prints them)
+KERNEL_NAMES = {"compress": "compress4_wide_kernel<0>", "decompress": "decompress4_wide_kernel<0>",
+                "reduce": "reduce_kernel<4, 4, false, false>"}
+MEASURED_TRAFFIC_BYTES = {"compress": 1208079826, "decompress": 1208387944, "reduce": 402904964}
+MEASURED_VALU_WAVE_INSTS = {"compress": 58195968, "decompress": 11468800, "reduce": 86425600}
 
 
 def algorithmic_bytes(kernel, n, rate, k=2):
@@ -178,12 +181,12 @@ def main():
         # two decodes and one encode per 6 bytes of traffic: bound by integer VALU work
         ops = MEASURED_VALU_WAVE_INSTS[dominant] * 64
         achieved = ops / (avg_ms[dominant] * 1e-3) / 1e12
-        roofline = {"kernel": dominant + "_kernel<%d>" % rate, "bound": "alu", "achieved": round(achieved, 2),
+        roofline = {"kernel": KERNEL_NAMES[dominant], "bound": "alu", "achieved": round(achieved, 2),
                     "peak": round(INT_ALU_PEAK_TOPS, 2), "unit": "Tops/s (int32 lane operations)",
                     "frac": round(achieved / INT_ALU_PEAK_TOPS, 4), "lane_ops_per_launch": ops}
     else:
         achieved = abytes / (avg_ms[dominant] * 1e-3) / 1e9
-        roofline = {"kernel": dominant + "_kernel<%d>" % rate, "bound": "hbm", "achieved": round(achieved, 1),
+        roofline = {"kernel": KERNEL_NAMES[dominant], "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
     roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_launch_ms": round(avg_ms[dominant], 4),
                      "algorithmic_bytes": abytes})
