@@ -279,6 +279,80 @@ int zc2d_ref_reduce_compressed(const void *const *in, int k, size_t rows, size_t
   return ZC2D_OK;
 }
 
+/* Sum of block (bi, bj) over the k inputs and, if `local` is given, the raw local values
+ * added last: ((d0 + d1) + ... + d_{k-1}) + x, one fp32 rounding per add.  Positions outside
+ * the matrix take no local value; they are filled or dropped by the caller. */
+static void sum_block2d(const void *const *in, int k, const float *local, size_t rows, size_t cols,
+                        size_t bi, size_t bj, int rate, float s[16]) {
+  size_t bc = (cols + 3) / 4, at = (bi * bc + bj) * (size_t)(2 * rate);
+  float d[16];
+  zc2d_ref_decode_block((const uint8_t *)in[0] + at, rate, s);
+  for (int c = 1; c < k; ++c) {
+    zc2d_ref_decode_block((const uint8_t *)in[c] + at, rate, d);
+    for (int i = 0; i < 16; ++i) {
+      volatile float t = s[i] + d[i];
+      s[i] = t;
+    }
+  }
+  if (local)
+    for (size_t r = 0; r < 4; ++r)
+      for (size_t q = 0; q < 4; ++q) {
+        size_t rr = 4 * bi + r, cc = 4 * bj + q;
+        if (rr < rows && cc < cols) {
+          volatile float t = s[4 * r + q] + local[rr * cols + cc];
+          s[4 * r + q] = t;
+        }
+      }
+}
+
+/* A ring hop whose local contribution is still a raw fp32 matrix (Sec. IV-A: each rank adds
+ * its own gradients to what it received before forwarding): out = compress(((d0 + ... +
+ * d_{k-1}) + local)), the edge fill taken from that sum.  local may be NULL. */
+int zc2d_ref_reduce_mixed(const void *const *in, int k, const float *local, size_t rows, size_t cols, int rate,
+                          void *out, size_t out_cap) {
+  if (!zc2d_ref_rate_supported(rate)) return ZC2D_ERR_RATE;
+  if (k < 1 || k > 16) return ZC2D_ERR_K;
+  if (rows == 0 || cols == 0) return ZC2D_OK;
+  if (!in || !out) return ZC2D_ERR_NULL;
+  for (int c = 0; c < k; ++c)
+    if (!in[c]) return ZC2D_ERR_NULL;
+  if (out_cap < zc2d_ref_compressed_size(rows, cols, rate)) return ZC2D_ERR_CAPACITY;
+  size_t bc = (cols + 3) / 4, br = (rows + 3) / 4;
+  for (size_t bi = 0; bi < br; ++bi)
+    for (size_t bj = 0; bj < bc; ++bj) {
+      float s[16], f[16];
+      sum_block2d(in, k, local, rows, cols, bi, bj, rate, s);
+      size_t rv = rows - 4 * bi < 4 ? rows - 4 * bi : 4, cv = cols - 4 * bj < 4 ? cols - 4 * bj : 4;
+      for (size_t r = 0; r < 4; ++r)
+        for (size_t q = 0; q < 4; ++q) f[4 * r + q] = s[4 * (r < rv ? r : rv - 1) + (q < cv ? q : cv - 1)];
+      zc2d_ref_encode_block(f, rate, (uint8_t *)out + (bi * bc + bj) * (size_t)(2 * rate));
+    }
+  return ZC2D_OK;
+}
+
+/* The last hop, where the sum is wanted as an fp32 matrix: nothing is re-encoded. */
+int zc2d_ref_reduce_decompress(const void *const *in, int k, const float *local, size_t rows, size_t cols, int rate,
+                               float *out) {
+  if (!zc2d_ref_rate_supported(rate)) return ZC2D_ERR_RATE;
+  if (k < 1 || k > 16) return ZC2D_ERR_K;
+  if (rows == 0 || cols == 0) return ZC2D_OK;
+  if (!in || !out) return ZC2D_ERR_NULL;
+  for (int c = 0; c < k; ++c)
+    if (!in[c]) return ZC2D_ERR_NULL;
+  size_t bc = (cols + 3) / 4, br = (rows + 3) / 4;
+  for (size_t bi = 0; bi < br; ++bi)
+    for (size_t bj = 0; bj < bc; ++bj) {
+      float s[16];
+      sum_block2d(in, k, local, rows, cols, bi, bj, rate, s);
+      for (size_t r = 0; r < 4; ++r)
+        for (size_t q = 0; q < 4; ++q) {
+          size_t rr = 4 * bi + r, cc = 4 * bj + q;
+          if (rr < rows && cc < cols) out[rr * cols + cc] = s[4 * r + q];
+        }
+    }
+  return ZC2D_OK;
+}
+
 /* ---- half-precision matrices ----------------------------------------------------------
  * bf16 / fp16 matrices (dtype codes as in zc_ref.c: 1 = bf16, 2 = fp16; the paper does not
  * state its message precision): every value is widened to fp32, which is exact, and the

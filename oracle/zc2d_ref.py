@@ -38,6 +38,10 @@ def lib():
                                           ctypes.c_void_p]
         L.zc2d_ref_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t,
                                                  ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+        L.zc2d_ref_reduce_mixed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                            ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+        L.zc2d_ref_reduce_decompress.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                                 ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
         L.zc2d_ref_compress_half.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int,
                                              ctypes.c_void_p, ctypes.c_size_t]
         L.zc2d_ref_decompress_half.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
@@ -161,4 +165,41 @@ def decompress_half(stream, rows, cols, rate, dtype):
     rc = lib().zc2d_ref_decompress_half(s.ctypes.data, int(rows), int(cols), int(rate), int(dtype), out.ctypes.data)
     if rc != 0:
         raise ValueError("zc2d_ref_decompress_half failed: %d" % rc)
+    return out
+
+
+def _pointers(streams, rows, cols, rate):
+    ss = [np.ascontiguousarray(s, dtype=np.uint8) for s in streams]
+    size = compressed_size(rows, cols, rate)
+    for s in ss:
+        if s.size < size:
+            raise ValueError("stream too short")
+    return ss, (ctypes.c_void_p * max(len(ss), 1))(*[s.ctypes.data for s in ss])
+
+
+def _local(local, rows, cols):
+    if local is None:
+        return None, None
+    a = np.ascontiguousarray(local, dtype=np.float32)
+    assert a.shape == (rows, cols)
+    return a, a.ctypes.data
+
+
+def reduce_mixed(streams, local, rows, cols, rate):
+    ss, ptrs = _pointers(streams, rows, cols, rate)
+    keep, lp = _local(local, rows, cols)
+    out = np.zeros(compressed_size(rows, cols, rate), dtype=np.uint8)
+    rc = lib().zc2d_ref_reduce_mixed(ptrs, len(ss), lp, int(rows), int(cols), int(rate), out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError("zc2d_ref_reduce_mixed failed: %d" % rc)
+    return out
+
+
+def reduce_decompress(streams, local, rows, cols, rate):
+    ss, ptrs = _pointers(streams, rows, cols, rate)
+    keep, lp = _local(local, rows, cols)
+    out = np.zeros((rows, cols), dtype=np.float32)
+    rc = lib().zc2d_ref_reduce_decompress(ptrs, len(ss), lp, int(rows), int(cols), int(rate), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("zc2d_ref_reduce_decompress failed: %d" % rc)
     return out

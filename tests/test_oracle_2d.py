@@ -266,3 +266,23 @@ def test_half_precision_matrices_are_compositions(o2, oracle, name):
         assert np.array_equal(o2.decompress_half(s, rows, cols, rate, code), want), (name, rate)
     with pytest.raises(ValueError):
         o2.compress_half(bits, 0, 4)
+
+
+@pytest.mark.parametrize("shape", [(8, 12), (7, 10), (2, 3)])
+def test_ring_hop_variants_are_compositions(o2, shape):
+    """reduce_mixed = compress(sum of decoded inputs + raw local matrix), reduce_decompress = that
+    sum itself, both spelled out with numpy fp32 adds in the stated order."""
+    from paper_2409_02423_amd import workloads
+    rows, cols = shape
+    local = workloads.gradient_lowrank(rows, cols, config=5, index=9).reshape(rows, cols)
+    for rate in (4, 16):
+        for k in (1, 2, 5):
+            comp = [o2.compress(workloads.gradient_lowrank(rows, cols, config=5, index=j).reshape(rows, cols), rate) for j in range(k)]
+            total = o2.decompress(comp[0], rows, cols, rate)
+            for c in comp[1:]:
+                total = (total + o2.decompress(c, rows, cols, rate)).astype(np.float32)
+            with_local = (total + local).astype(np.float32)
+            assert np.array_equal(o2.reduce_decompress(comp, local, rows, cols, rate).view(np.uint32), with_local.view(np.uint32))
+            assert np.array_equal(o2.reduce_decompress(comp, None, rows, cols, rate).view(np.uint32), total.view(np.uint32))
+            assert np.array_equal(o2.reduce_mixed(comp, local, rows, cols, rate), o2.compress(with_local, rate))
+            assert np.array_equal(o2.reduce_mixed(comp, None, rows, cols, rate), o2.reduce_compressed(comp, rows, cols, rate))
