@@ -201,6 +201,16 @@ int zc2d_decompress_half(const void* d_in, size_t rows, size_t cols, int rate, i
 int zc2d_reduce_compressed(const void* const* d_in, int k, size_t rows, size_t cols, int rate, void* d_out,
                            size_t out_cap, void* stream);
 
+/* The ring hops of the reduce-scatter on matrix-shaped messages, as zc_reduce_mixed and
+ * zc_reduce_decompress (Sec. IV-A): the compressed form, respectively the fp32 matrix, of
+ * ((x_0 + ... + x_{k-1}) + local), x_j the decompressed matrix j, local a raw row-major fp32
+ * matrix of the same shape that may be NULL.  The compressed output may be one of the inputs
+ * d_in[j]; the fp32 output may be the same buffer as d_local; no other overlap. */
+int zc2d_reduce_mixed(const void* const* d_in, int k, const float* d_local, size_t rows, size_t cols, int rate, void* d_out,
+                      size_t out_cap, void* stream);
+int zc2d_reduce_decompress(const void* const* d_in, int k, const float* d_local, size_t rows, size_t cols, int rate,
+                           float* d_out, void* stream);
+
 /*
  * Lossless messages, format "ZL-1": the role the paper's first hybrid scheme gives to a
  * lossless codec of the MPC kind on model-parallel traffic (Sec. II-A, Sec. III-A and its

@@ -234,8 +234,11 @@ struct ChunkPointers2d {
 // The reduce-scatter step on matrix-shaped messages: block b of the k chunks is decoded,
 // the 16 values are added in registers in chunk order, and the sum is encoded; where the
 // block sticks out of the matrix its fill is taken from the sum's last valid row / column.
-template <int RATE>
-__global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chunks, int k, Walk w, uint8_t* out) {
+// LOCAL: a raw fp32 matrix is added last (a ring hop's own contribution); RAW_OUT: the sum
+// is stored as an fp32 matrix instead of being encoded (the last hop).
+template <int RATE, bool LOCAL, bool RAW_OUT>
+__global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chunks, int k, const float* local, Walk w,
+                                                            uint8_t* out, float* out_raw) {
   __shared__ __attribute__((aligned(16))) uint32_t expand[256];
   __shared__ __attribute__((aligned(16))) uint32_t token[zc2d::kTokenRows << zc2d::kLookahead];
   for (int i = threadIdx.x; i < 256 / 4; i += kThreads)
@@ -262,6 +265,20 @@ __global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chun
       zc2d::decode_block<RATE>(W, token, y, AnyLane());
 #pragma unroll
       for (int i = 0; i < 16; ++i) sum[i] += y[i];
+    }
+    if constexpr (LOCAL) {
+      // (where the block sticks out of the matrix the clamped loads add copies of edge values;
+      // those positions are refilled from the sum or dropped below)
+      uint32_t mine[16];
+      load_block<kF32>(local, w, cur, mine);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sum[i] += __uint_as_float(mine[i]);
+    }
+    if constexpr (RAW_OUT) {
+      store_block<kF32>(out_raw, w, cur, sum);
+      cur.advance(w);
+      if (cur.b >= w.blocks) break;
+      continue;
     }
     uint32_t x[16];
     if (cur.whole(w) || (4 * cur.bi + 4 <= w.rows && 4 * cur.bj + 4 <= w.cols)) {
@@ -383,6 +400,43 @@ int launch_decompress2d(const void* d_in, size_t rows, size_t cols, int rate, vo
   return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
 }
 
+int launch_reduce2d(const void* const* d_in, int k, const float* d_local, size_t rows, size_t cols, int rate, void* d_out,
+                    size_t out_cap, float* d_out_raw, void* stream) {
+  const bool raw_out = d_out_raw != nullptr;
+  if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
+  if (k < 1 || k > 16) return ZC_ERR_K;
+  if (rows == 0 || cols == 0) return ZC_OK;
+  if (!d_in || (!raw_out && !d_out)) return ZC_ERR_NULL;
+  ChunkPointers2d chunks;
+  for (int j = 0; j < 16; ++j) chunks.p[j] = nullptr;
+  for (int j = 0; j < k; ++j) {
+    if (!d_in[j]) return ZC_ERR_NULL;
+    if (!aligned16(d_in[j])) return ZC_ERR_ALIGN;
+    chunks.p[j] = static_cast<const uint8_t*>(d_in[j]);
+  }
+  if (!aligned16(d_out) || !aligned16(d_out_raw) || !aligned16(d_local)) return ZC_ERR_ALIGN;
+  if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
+  if (!raw_out && out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
+  const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const unsigned grid = grid_for(blocks);
+  const Walk w = walk_for(rows, cols, grid);
+  uint8_t* out = static_cast<uint8_t*>(d_out);
+#define LAUNCH(R, LOCAL, RAW) \
+  hipLaunchKernelGGL((reduce2d_kernel<R, LOCAL, RAW>), dim3(grid), dim3(kThreads), 0, s, chunks, k, d_local, w, out, d_out_raw)
+#define CALL(R)                                    \
+  do {                                             \
+    if (d_local && raw_out) LAUNCH(R, true, true); \
+    else if (d_local) LAUNCH(R, true, false);      \
+    else if (raw_out) LAUNCH(R, false, true);      \
+    else LAUNCH(R, false, false);                  \
+  } while (0)
+  ZC2D_DISPATCH_RATE(rate, CALL)
+#undef CALL
+#undef LAUNCH
+  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -417,28 +471,18 @@ int zc2d_decompress_half(const void* d_in, size_t rows, size_t cols, int rate, i
 
 int zc2d_reduce_compressed(const void* const* d_in, int k, size_t rows, size_t cols, int rate, void* d_out,
                            size_t out_cap, void* stream) {
-  if (!zc2d_rate_supported(rate)) return ZC_ERR_RATE;
-  if (k < 1 || k > 16) return ZC_ERR_K;
-  if (rows == 0 || cols == 0) return ZC_OK;
-  if (!d_in || !d_out) return ZC_ERR_NULL;
-  ChunkPointers2d chunks;
-  for (int j = 0; j < 16; ++j) chunks.p[j] = nullptr;
-  for (int j = 0; j < k; ++j) {
-    if (!d_in[j]) return ZC_ERR_NULL;
-    if (!aligned16(d_in[j])) return ZC_ERR_ALIGN;
-    chunks.p[j] = static_cast<const uint8_t*>(d_in[j]);
-  }
-  if (!aligned16(d_out)) return ZC_ERR_ALIGN;
-  if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
-  if (out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
-  const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned grid = grid_for(blocks);
-  const Walk w = walk_for(rows, cols, grid);
-#define CALL(R) hipLaunchKernelGGL(reduce2d_kernel<R>, dim3(grid), dim3(kThreads), 0, s, chunks, k, w, static_cast<uint8_t*>(d_out))
-  ZC2D_DISPATCH_RATE(rate, CALL)
-#undef CALL
-  return hipGetLastError() == hipSuccess ? ZC_OK : ZC_ERR_LAUNCH;
+  return launch_reduce2d(d_in, k, nullptr, rows, cols, rate, d_out, out_cap, nullptr, stream);
+}
+
+int zc2d_reduce_mixed(const void* const* d_in, int k, const float* d_local, size_t rows, size_t cols, int rate, void* d_out,
+                      size_t out_cap, void* stream) {
+  return launch_reduce2d(d_in, k, d_local, rows, cols, rate, d_out, out_cap, nullptr, stream);
+}
+
+int zc2d_reduce_decompress(const void* const* d_in, int k, const float* d_local, size_t rows, size_t cols, int rate,
+                           float* d_out, void* stream) {
+  if (zc2d_rate_supported(rate) && k >= 1 && k <= 16 && rows != 0 && cols != 0 && !d_out) return ZC_ERR_NULL;
+  return launch_reduce2d(d_in, k, d_local, rows, cols, rate, nullptr, 0, d_out, stream);
 }
 
 }  // extern "C"

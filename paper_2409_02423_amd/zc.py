@@ -24,7 +24,7 @@ EXPORTS = ("zc_version", "zc_strerror", "zc_rate_supported", "zc_rate_for_class"
            "zc_compress", "zc_decompress", "zc_reduce_compressed", "zc_reduce_mixed", "zc_reduce_decompress",
            "zc_compress_half", "zc_decompress_half",
            "zc2d_rate_supported", "zc2d_compressed_size", "zc2d_compress", "zc2d_decompress", "zc2d_reduce_compressed",
-           "zc2d_compress_half", "zc2d_decompress_half",
+           "zc2d_compress_half", "zc2d_decompress_half", "zc2d_reduce_mixed", "zc2d_reduce_decompress",
            "zl_max_compressed_size", "zl_compress", "zl_stream_bytes", "zl_decompress", "zl_compress16", "zl_decompress16")
 
 _lib = None
@@ -82,6 +82,10 @@ def lib():
                                            ctypes.c_void_p, ctypes.c_void_p]
         L.zc2d_reduce_compressed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                              ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.zc2d_reduce_mixed.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                        ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.zc2d_reduce_decompress.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                             ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.zl_max_compressed_size.restype = ctypes.c_size_t
         L.zl_max_compressed_size.argtypes = [ctypes.c_size_t]
         L.zl_compress.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
@@ -399,6 +403,59 @@ def zc2d_reduce_compressed(d_in, rows, cols, rate, d_out=None, stream=None):
                                       _stream_handle(stream))
     if rc != ZC_OK:
         raise ZcError(rc, "zc2d_reduce_compressed")
+    return d_out
+
+
+def _chunks2d(d_in, rows, cols, rate, what):
+    chunks = list(d_in)
+    need = zc2d_compressed_size(rows, cols, rate)
+    if need == 0 and rows * cols != 0:
+        raise ZcError(ZC_ERR_RATE, what)
+    for c in chunks:
+        _check_device_tensor(c, torch.uint8, "every chunk")
+        if c.numel() < need:
+            raise ValueError("a chunk holds %d bytes, need %d" % (c.numel(), need))
+    return chunks, need, (ctypes.c_void_p * max(len(chunks), 1))(*[c.data_ptr() for c in chunks])
+
+
+def _local2d(d_local, rows, cols):
+    if d_local is None:
+        return None
+    _check_device_tensor(d_local, torch.float32, "d_local")
+    if tuple(d_local.shape) != (rows, cols):
+        raise ValueError("d_local must have shape (%d, %d)" % (rows, cols))
+    return d_local.data_ptr()
+
+
+def zc2d_reduce_mixed(d_in, d_local, rows, cols, rate, d_out=None, stream=None):
+    """k compressed matrices plus a raw fp32 matrix (or None) -> compressed sum."""
+    chunks, need, ptrs = _chunks2d(d_in, rows, cols, rate, "zc2d_reduce_mixed")
+    local = _local2d(d_local, rows, cols)
+    if d_out is None:
+        device = chunks[0].device if chunks else torch.device("cuda")
+        d_out = torch.empty(need, dtype=torch.uint8, device=device)
+    _check_device_tensor(d_out, torch.uint8, "d_out")
+    rc = lib().zc2d_reduce_mixed(ptrs, len(chunks), local, int(rows), int(cols), int(rate), d_out.data_ptr(), d_out.numel(),
+                                 _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_reduce_mixed")
+    return d_out
+
+
+def zc2d_reduce_decompress(d_in, d_local, rows, cols, rate, d_out=None, stream=None):
+    """k compressed matrices plus a raw fp32 matrix (or None) -> fp32 sum of shape (rows, cols)."""
+    chunks, need, ptrs = _chunks2d(d_in, rows, cols, rate, "zc2d_reduce_decompress")
+    local = _local2d(d_local, rows, cols)
+    if d_out is None:
+        device = chunks[0].device if chunks else torch.device("cuda")
+        d_out = torch.empty((rows, cols), dtype=torch.float32, device=device)
+    _check_device_tensor(d_out, torch.float32, "d_out")
+    if d_out.numel() < rows * cols:
+        raise ValueError("d_out holds %d values, need %d" % (d_out.numel(), rows * cols))
+    rc = lib().zc2d_reduce_decompress(ptrs, len(chunks), local, int(rows), int(cols), int(rate), d_out.data_ptr(),
+                                      _stream_handle(stream))
+    if rc != ZC_OK:
+        raise ZcError(rc, "zc2d_reduce_decompress")
     return d_out
 
 

@@ -219,6 +219,33 @@ def test_half_precision_matrices(gpu, ref, name):
     assert gpu.lib().zc2d_decompress_half(0x10000, 4, 4, 4, 7, 0x10000, None) == gpu.ZC_ERR_DTYPE
 
 
+@pytest.mark.parametrize("rate", (4, 16))
+def test_ring_hop_variants_match_reference(gpu, ref, rate):
+    import torch
+    for rows, cols in ((64, 256), (61, 1027), (2, 3)):
+        mats = [_matrix(rows, cols, seed=20 + j) for j in range(3)]
+        local = _matrix(rows, cols, seed=29)
+        comp = [ref.compress(m, rate) for m in mats]
+        dcomp = [_dev(c) for c in comp]
+        dlocal = _dev(local)
+        for k in (1, 2, 3):
+            print("2d ring hop rate", rate, "shape", rows, cols, "k", k, flush=True)
+            for loc, dloc in ((local, dlocal), (None, None)):
+                got = gpu.zc2d_reduce_mixed(dcomp[:k], dloc, rows, cols, rate)
+                _same_bytes(_host(got), ref.reduce_mixed(comp[:k], loc, rows, cols, rate), rate, "mixed k%d" % k)
+                raw = gpu.zc2d_reduce_decompress(dcomp[:k], dloc, rows, cols, rate)
+                _same_floats(_host(raw), ref.reduce_decompress(comp[:k], loc, rows, cols, rate), "to raw k%d" % k)
+        # the fp32 output over the local matrix, as the last hop of a ring would do it
+        acc = dlocal.clone()
+        gpu.zc2d_reduce_decompress(dcomp[:2], acc, rows, cols, rate, d_out=acc)
+        _same_floats(_host(acc), ref.reduce_decompress(comp[:2], local, rows, cols, rate), "in place over local")
+    with pytest.raises(gpu.ZcError) as e:
+        gpu.zc2d_reduce_mixed([], None, 8, 8, 4)
+    assert e.value.code == gpu.ZC_ERR_K
+    assert gpu.lib().zc2d_reduce_decompress(None, 1, None, 8, 8, 4, None, None) == gpu.ZC_ERR_NULL
+    torch.cuda.synchronize()
+
+
 def test_reduce_errors(gpu):
     import torch
     c = torch.zeros(gpu.zc2d_compressed_size(8, 8, 4), dtype=torch.uint8, device="cuda")
