@@ -29,7 +29,9 @@ __device__ __forceinline__ void stage_table(const uint32_t* __restrict__ src, ui
     reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(src)[i];
   __syncthreads();
 }
-constexpr int kWorkgroupsPerCU = 16;   // ZC2D_WORKGROUPS_PER_CU overrides this for tuning runs
+// Workgroups per CU in the grid (measured: the decoder-bound kernels like a few more than
+// the compress kernel).  ZC2D_WORKGROUPS_PER_CU overrides both for tuning runs.
+constexpr int kCompressWorkgroupsPerCU = 16, kDecodeWorkgroupsPerCU = 32;
 
 struct AnyLane {
   __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
@@ -319,7 +321,7 @@ int compute_units() {
   return cus;
 }
 
-int workgroups_per_cu() {
+int workgroups_per_cu(int preset) {
   static int forced = -1;
   if (forced < 0) {
     forced = 0;
@@ -328,12 +330,12 @@ int workgroups_per_cu() {
       if (v >= 1 && v <= 4096) forced = v;
     }
   }
-  return forced > 0 ? forced : kWorkgroupsPerCU;
+  return forced > 0 ? forced : preset;
 }
 
-unsigned grid_for(size_t blocks) {
+unsigned grid_for(size_t blocks, int preset) {
   const size_t groups = (blocks + kThreads - 1) / kThreads;
-  const size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu();
+  const size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu(preset);
   return (unsigned)(groups < cap ? groups : cap);
 }
 
@@ -375,7 +377,7 @@ int launch_compress2d(const void* d_in, size_t rows, size_t cols, int rate, void
   if (out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
   const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned grid = grid_for(blocks);
+  const unsigned grid = grid_for(blocks, kCompressWorkgroupsPerCU);
   const Walk w = walk_for(rows, cols, grid);
 #define CALL(R) hipLaunchKernelGGL((compress2d_kernel<R, DT>), dim3(grid), dim3(kThreads), 0, s, d_in, w, static_cast<uint8_t*>(d_out))
   ZC2D_DISPATCH_RATE(rate, CALL)
@@ -392,7 +394,7 @@ int launch_decompress2d(const void* d_in, size_t rows, size_t cols, int rate, vo
   if (rows > kMaxValues || cols > kMaxValues || rows > kMaxValues / cols) return ZC_ERR_SIZE;
   const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned grid = grid_for(blocks);
+  const unsigned grid = grid_for(blocks, kDecodeWorkgroupsPerCU);
   const Walk w = walk_for(rows, cols, grid);
 #define CALL(R) hipLaunchKernelGGL((decompress2d_kernel<R, DT>), dim3(grid), dim3(kThreads), 0, s, static_cast<const uint8_t*>(d_in), w, d_out)
   ZC2D_DISPATCH_RATE(rate, CALL)
@@ -419,7 +421,7 @@ int launch_reduce2d(const void* const* d_in, int k, const float* d_local, size_t
   if (!raw_out && out_cap < zc2d_compressed_size(rows, cols, rate)) return ZC_ERR_CAPACITY;
   const size_t blocks = ((rows + 3) / 4) * ((cols + 3) / 4);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned grid = grid_for(blocks);
+  const unsigned grid = grid_for(blocks, kDecodeWorkgroupsPerCU);
   const Walk w = walk_for(rows, cols, grid);
   uint8_t* out = static_cast<uint8_t*>(d_out);
 #define LAUNCH(R, LOCAL, RAW) \
