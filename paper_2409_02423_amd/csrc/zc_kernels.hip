@@ -409,9 +409,10 @@ struct ChunkPointers {
 // visited chunk by chunk, (tile, chunk 0), (tile, chunk 1), ..., (next tile, chunk 0),
 // and the next one in that order is fetched before the current one is decoded; the
 // local values of a tile are requested before its first chunk is decoded.
-template <int RATE, int U, bool LOCAL, bool RAW_OUT>
-__global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k, const float* local, size_t n,
+template <int RATE, int U, bool LOCAL, bool RAW_OUT, int K>
+__global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, int k_given, const float* local, size_t n,
                                                           uint8_t* out, float* out_raw) {
+  const int k = K > 0 ? K : k_given;   // K > 0: the number of chunks is known when the kernel is compiled
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
   __shared__ __align__(16) uint32_t enc[RAW_OUT ? 4 : encoder_table_words<RATE>()];
   if constexpr (!RAW_OUT) stage_encoder_table<RATE>(enc);
@@ -453,6 +454,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
         for (int u = 0; u < U; ++u) load_values<kF32>(local, t * kTile + u * kThreads + threadIdx.x, loc[u]);
       }
       float s[U][4];
+#pragma unroll
       for (int c = 0; c < k; ++c) {
         const bool last = c + 1 == k;
         const uint8_t* src = chunks.p[last ? 0 : c + 1];
@@ -749,9 +751,14 @@ static int launch_reduce(const void* const* d_in, int k, const float* d_local, s
   if (!raw_out && out_cap < zc_compressed_size(n, rate)) return ZC_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint8_t* out = static_cast<uint8_t*>(d_out);
-#define LAUNCH(R, LOCAL, RAW)                                                                                 \
-  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW>), dim3(grid_for(n, kReduce, R)),       \
+#define LAUNCH_K(R, LOCAL, RAW, K)                                                                            \
+  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW, K>), dim3(grid_for(n, kReduce, R)),    \
                      dim3(kThreads), 0, s, chunks, k, d_local, n, out, d_out_raw)
+#define LAUNCH(R, LOCAL, RAW)                 \
+  do {                                        \
+    if (k == 2) LAUNCH_K(R, LOCAL, RAW, 2);   \
+    else LAUNCH_K(R, LOCAL, RAW, 0);          \
+  } while (0)
 #define CALL(R)                                   \
   do {                                            \
     if (d_local && raw_out) LAUNCH(R, true, true);        \
@@ -762,6 +769,7 @@ static int launch_reduce(const void* const* d_in, int k, const float* d_local, s
   ZC_DISPATCH_RATE(rate, CALL)
 #undef CALL
 #undef LAUNCH
+#undef LAUNCH_K
   return finish_launch();
 }
 
