@@ -24,9 +24,22 @@ def is_stale():
 
 
 def build(extra_flags=(), out=None):
+    """Compile every source (in parallel, one hipcc each) and link them into the library."""
+    from concurrent.futures import ThreadPoolExecutor
+    import tempfile
     out = out or LIB
-    tmp = out + ".tmp.%d" % os.getpid()
-    subprocess.check_call([HIPCC] + FLAGS + list(extra_flags) + SOURCES + ["-o", tmp])
+    compile_flags = [f for f in FLAGS if f != "-shared"] + list(extra_flags)
+    with tempfile.TemporaryDirectory(prefix="zc_build_") as work:
+        objects = [os.path.join(work, os.path.basename(src) + ".o") for src in SOURCES]
+
+        def compile_one(pair):
+            src, obj = pair
+            subprocess.check_call([HIPCC] + compile_flags + ["-c", src, "-o", obj])
+
+        with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+            list(pool.map(compile_one, zip(SOURCES, objects)))
+        tmp = out + ".tmp.%d" % os.getpid()
+        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objects + ["-o", tmp])
     os.replace(tmp, out)
     return out
 
