@@ -219,8 +219,8 @@ constexpr int32_t from_negabinary(uint32_t u) { return (int32_t)((u ^ 0xAAAAAAAA
 
 // Rate 4: the payload is one byte, so everything between the header and the final
 // scaling is a function of 256 cases.  Entry = the four fixed-point values of the
-// block as floats (4 floats per payload value); they are multiples of 2^22 below
-// 2^31 in magnitude, hence exact in fp32.  Eight payload bits reach at most planes
+// block divided by 2^22, as floats (4 floats per payload value): the values are multiples
+// of 2^22 below 2^31 in magnitude, so the entries are small integers.  Eight payload bits reach at most planes
 // 31..24 of the coefficient words.
 struct Dec4Table { float v[256 * 4]; };
 
@@ -239,10 +239,12 @@ constexpr Dec4Table build_dec4_table() {
     }
     int32_t a = from_negabinary(u[0]), b = from_negabinary(u[1]), c = from_negabinary(u[2]), d = from_negabinary(u[3]);
     inverse_lift(a, b, c, d);
-    t.v[4 * payload + 0] = (float)a;
-    t.v[4 * payload + 1] = (float)b;
-    t.v[4 * payload + 2] = (float)c;
-    t.v[4 * payload + 3] = (float)d;
+    // multiples of 2^22 (the inverse lifting shifts multiples of 2^24 right by at most 2): kept
+    // as that multiple, an integer below 2^9 in magnitude
+    t.v[4 * payload + 0] = (float)(a >> 22);
+    t.v[4 * payload + 1] = (float)(b >> 22);
+    t.v[4 * payload + 2] = (float)(c >> 22);
+    t.v[4 * payload + 3] = (float)(d >> 22);
   }
   return t;
 }
@@ -427,7 +429,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     // one lookup for the whole payload byte (entry 0 is the zero block, which ignores
     // its payload), then only the scaling by 2^(E - 155) is left
     const float* q = tab.dec4 + 4u * (E ? W[0] >> 8 : 0u);
-    const int ex = (int)E - 127 - kFractionBits;
+    const int ex = (int)E - 127 - kFractionBits + 22;
 #pragma unroll
     for (int i = 0; i < 4; ++i) out[i] = __builtin_ldexpf(q[i], ex);
   } else {
@@ -524,6 +526,18 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     }
     inverse_transform(u, E, out);
   }
+}
+
+// Rate 4: sum += the decoded block, with one rounding per value as a decode followed by an
+// add would give: the table's entries are integers below 2^9 and 2^(E - 133) is a
+// representable (possibly subnormal) power of two, so their product is exact and the fused
+// multiply-add rounds the same sum once.
+ZC_DEV void accumulate_block4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
+  const uint32_t E = W0 & 0xFFu;
+  const float* q = tab.dec4 + 4u * (E ? W0 >> 8 : 0u);
+  const float scale = __builtin_ldexpf(1.0f, (int)E - 127 - kFractionBits + 22);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) sum[i] = __builtin_fmaf(q[i], scale, sum[i]);
 }
 
 }  // namespace zc

@@ -464,10 +464,14 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
         for (int u = 0; u < U; ++u) load_stream<RATE>(src, next + u * kThreads, Wn[u]);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          float y[4];
-          zc::decode_block<RATE>(W[u], tab, y, AnyLane());
+          if (RATE == 4 && c > 0) {
+            zc::accumulate_block4(W[u][0], tab, s[u]);
+          } else {
+            float y[4];
+            zc::decode_block<RATE>(W[u], tab, y, AnyLane());
 #pragma unroll
-          for (int i = 0; i < 4; ++i) s[u][i] = c ? s[u][i] + y[i] : y[i];
+            for (int i = 0; i < 4; ++i) s[u][i] = c ? s[u][i] + y[i] : y[i];
+          }
 #pragma unroll
           for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
         }
