@@ -31,8 +31,8 @@ INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one
 # the kernels behind the three calls of the step at rate 4 (names as rocprofv3 prints them)
 KERNEL_NAMES = {"compress": "compress4_wide_kernel<0>", "decompress": "decompress4_wide_kernel<0>",
                 "reduce": "reduce_kernel<4, 4, false, false, 2>"}
-MEASURED_TRAFFIC_BYTES = {"compress": 1208079826, "decompress": 1208387944, "reduce": 402904964}
-MEASURED_VALU_WAVE_INSTS = {"compress": 58195968, "decompress": 11468800, "reduce": 86425600}
+MEASURED_TRAFFIC_BYTES = {"compress": 1208070461, "decompress": 1208412093, "reduce": 402873520}
+MEASURED_VALU_WAVE_INSTS = {"compress": 58195968, "decompress": 11468800, "reduce": 79101952}
 
 
 def algorithmic_bytes(kernel, n, rate, k=2):
