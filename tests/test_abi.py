@@ -161,3 +161,20 @@ def test_lossless_sizes_and_argument_errors():
     assert L.zl_decompress(good, 64, 100, odd, None) == zc.ZC_ERR_ALIGN
     assert L.zl_decompress(good, 32, 0, None, None) == zc.ZC_OK                  # empty message: nothing to write
     assert L.zl_stream_bytes(None, None, None) == zc.ZC_ERR_NULL
+
+
+def test_no_fallback_when_the_library_is_missing(monkeypatch, tmp_path):
+    """Without the built library (and without a compiler to build it) every call raises: there
+    is no other path."""
+    from paper_2409_02423_amd import build as b
+    monkeypatch.setattr(zc, "_lib", None)
+    monkeypatch.setattr(b, "LIB", str(tmp_path / "libzc_missing.so"))
+
+    def refuse(*a, **k):
+        raise RuntimeError("no compiler here")
+
+    monkeypatch.setattr(b, "build", refuse)
+    with pytest.raises(RuntimeError):
+        zc.zc_version()
+    with pytest.raises(RuntimeError):
+        zc.zc_compressed_size(16, 4)
