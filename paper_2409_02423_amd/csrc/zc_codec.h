@@ -489,26 +489,51 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
             left -= len;
             state = e & 0x7000u;
           };
+          if constexpr (RATE < 12) {
 #pragma unroll 1
-          for (; m < 4u; ++m) {
-            if (!any_lane_active(left > 0)) break;
-            one_plane();
-          }
-          if (m == 4u) {
-            if (RATE >= 12 && !any_lane_active(left > 0 && state < 0x3000u)) {
-              // the same in the middle of a group: its last four planes from 16 stream bits
-              const uint32_t len = umin(left, 16u);
-              const uint32_t bits = (W[0] >> 2) & ((1u << len) - 1u);
-              const uint32_t* pair = tab.dec + kDecPlaneEntries;
-              acc = acc << 4 | pair[bits & 0xFFu] << 2 | pair[bits >> 8];
-              shift_out<NW>(W, len);
-              left -= len;
-              m = 8u;
-            } else {
+            for (; m < 8u; ++m) {
+              if (!any_lane_active(left > 0)) break;
+              one_plane();
+            }
+          } else {
 #pragma unroll 1
-              for (; m < 8u; ++m) {
-                if (!any_lane_active(left > 0)) break;
-                one_plane();
+            for (; m < 4u; ++m) {
+              if (!any_lane_active(left > 0)) break;
+              one_plane();
+            }
+            if (m == 4u) {
+              if (!any_lane_active(left > 0 && state < 0x3000u)) {
+                // the same in the middle of a group: its last four planes from 16 stream bits
+                const uint32_t len = umin(left, 16u);
+                const uint32_t bits = (W[0] >> 2) & ((1u << len) - 1u);
+                const uint32_t* pair = tab.dec + kDecPlaneEntries;
+                acc = acc << 4 | pair[bits & 0xFFu] << 2 | pair[bits >> 8];
+                shift_out<NW>(W, len);
+                left -= len;
+                m = 8u;
+              } else {
+#pragma unroll 1
+                for (; m < 6u; ++m) {
+                  if (!any_lane_active(left > 0)) break;
+                  one_plane();
+                }
+                if (m == 6u) {
+                  if (!any_lane_active(left > 0 && state < 0x3000u)) {
+                    // and once more before its last two planes
+                    const uint32_t len = umin(left, 8u);
+                    const uint32_t bits = (W[0] >> 2) & ((1u << len) - 1u);
+                    acc = acc << 2 | tab.dec[kDecPlaneEntries + bits];
+                    shift_out<NW>(W, len);
+                    left -= len;
+                    m = 8u;
+                  } else {
+#pragma unroll 1
+                    for (; m < 8u; ++m) {
+                      if (!any_lane_active(left > 0)) break;
+                      one_plane();
+                    }
+                  }
+                }
               }
             }
           }
