@@ -89,6 +89,18 @@ int zc2d_ref_block_exponent(const float x[16]) {
   return emax + 127;
 }
 
+/* q_i = x_i * 2^(27 - e), truncated toward zero.  The product is exact in double. */
+void zc2d_ref_quantise(const float x[16], int E, int32_t q[16]) {
+  for (int i = 0; i < 16; ++i)
+    q[i] = (int32_t)trunc(ldexp((double)x[i], ZC2D_FRACTION_BITS - (E - 127)));
+}
+
+/* x_i = float(q_i) * 2^(e - 27): int -> fp32 with round-to-nearest-even, then an IEEE
+ * scaling by a power of two (rounds a second time only for subnormal results). */
+void zc2d_ref_dequantise(const int32_t q[16], int E, float x[16]) {
+  for (int i = 0; i < 16; ++i) x[i] = ldexpf((float)q[i], (E - 127) - ZC2D_FRACTION_BITS);
+}
+
 /* v is the 4x4 block, row-major: lifting along each row, then along each column. */
 void zc2d_ref_fwd_transform(int32_t v[16]) {
   for (int r = 0; r < 4; ++r) zc_ref_fwd_lift(v + 4 * r);
@@ -173,8 +185,7 @@ void zc2d_ref_encode_block(const float x[16], int rate, uint8_t *out /* 2*rate b
   if (E == 0) return;
   out[0] = (uint8_t)E;
   int32_t q[16];
-  for (int i = 0; i < 16; ++i)
-    q[i] = (int32_t)trunc(ldexp((double)x[i], ZC2D_FRACTION_BITS - (E - 127)));
+  zc2d_ref_quantise(x, E, q);
   zc2d_ref_fwd_transform(q);
   int order[16];
   zc2d_ref_order(order);
@@ -198,7 +209,7 @@ void zc2d_ref_decode_block(const uint8_t *in, int rate, float x[16]) {
   int32_t q[16];
   for (int c = 0; c < 16; ++c) q[order[c]] = zc_ref_inv_negabinary(u[c]);
   zc2d_ref_inv_transform(q);
-  for (int i = 0; i < 16; ++i) x[i] = ldexpf((float)q[i], (E - 127) - ZC2D_FRACTION_BITS);
+  zc2d_ref_dequantise(q, E, x);
 }
 
 /* ---- whole matrices (host pointers) -------------------------------------- */

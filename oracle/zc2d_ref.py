@@ -21,6 +21,10 @@ def lib():
         L.zc2d_ref_order.argtypes = [_i32p]
         L.zc2d_ref_order.restype = None
         L.zc2d_ref_block_exponent.argtypes = [_f32p]
+        L.zc2d_ref_quantise.argtypes = [_f32p, ctypes.c_int, _i32p]
+        L.zc2d_ref_quantise.restype = None
+        L.zc2d_ref_dequantise.argtypes = [_i32p, ctypes.c_int, _f32p]
+        L.zc2d_ref_dequantise.restype = None
         L.zc2d_ref_fwd_transform.argtypes = [_i32p]
         L.zc2d_ref_fwd_transform.restype = None
         L.zc2d_ref_inv_transform.argtypes = [_i32p]
@@ -63,6 +67,20 @@ def order():
 def block_exponent(x16):
     x = np.ascontiguousarray(x16, dtype=np.float32).reshape(16)
     return int(lib().zc2d_ref_block_exponent(x.ctypes.data_as(_f32p)))
+
+
+def quantise(x16, E):
+    x = np.ascontiguousarray(x16, dtype=np.float32).reshape(16)
+    q = np.zeros(16, dtype=np.int32)
+    lib().zc2d_ref_quantise(x.ctypes.data_as(_f32p), int(E), q.ctypes.data_as(_i32p))
+    return q
+
+
+def dequantise(q16, E):
+    q = np.array(q16, dtype=np.int64).astype(np.int32).reshape(16)
+    x = np.zeros(16, dtype=np.float32)
+    lib().zc2d_ref_dequantise(q.ctypes.data_as(_i32p), int(E), x.ctypes.data_as(_f32p))
+    return x
 
 
 def fwd_transform(v16):

@@ -69,6 +69,89 @@ def test_transform_is_separable_basis_matrix(o2):
     assert list(o2.fwd_transform([c] * 16)) == [c] + [0] * 15
 
 
+def _golden_2d(kind):
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "zc2d_vectors.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                parts = [p.strip() for p in line.split(";")]
+                if (parts[0] == "D") == (kind == "D"):
+                    rows.append(parts)
+    return rows
+
+
+def test_transform_order_hand_derived_blocks(o2):
+    """Rows first, then columns, on blocks small enough that the floors of the lifting steps
+    make the order (and the row-major indexing) visible; expected values derived by hand in
+    tests/golden/zc2d_vectors.txt."""
+    rows = _golden_2d("T")
+    assert len(rows) == 2
+    for name, block, want in rows:
+        x = [int(t) for t in block.split()]
+        w = [int(t) for t in want.split()]
+        got = o2.fwd_transform(x)
+        assert list(got) == w, name
+        assert list(o2.inv_transform(w)) == x, name
+        # the other order gives another answer on these blocks, so the pin discriminates
+        xt = list(np.array(x).reshape(4, 4).T.reshape(16))
+        other = list(np.array(o2.fwd_transform(xt)).reshape(4, 4).T.reshape(16))
+        assert other != w, name
+
+
+def test_quantise_is_exact_truncation(o2):
+    """q = trunc(x * 2^(27-e)) in exact rational arithmetic: toward zero for negative values
+    whose scaled magnitude is not an integer."""
+    rng = np.random.default_rng(56)
+    seen_negative_inexact = 0
+    for trial in range(300):
+        spread = rng.integers(0, 30, size=16)
+        blk = (rng.standard_normal(16) * np.ldexp(1.0, -spread.astype(int)) * 10.0 ** rng.integers(-30, 30)).astype(np.float32)
+        if trial % 7 == 0:
+            blk[rng.integers(0, 16)] = 0.0
+        E = o2.block_exponent(blk)
+        if E == 0:
+            continue
+        q = o2.quantise(blk, E)
+        for xi, qi in zip(blk, q):
+            exact = Fraction(float(xi)) * Fraction(2) ** (27 - (E - 127))
+            t = int(abs(exact))   # floor of the magnitude
+            assert int(qi) == (t if exact >= 0 else -t), (xi, E, qi)
+            seen_negative_inexact += exact < 0 and exact.denominator != 1
+        assert np.abs(q.astype(np.int64)).max() <= M
+        if E > 1:
+            assert np.abs(q.astype(np.int64)).max() >= 1 << 26
+    assert seen_negative_inexact > 500
+    # written out: -0.3 next to 1.0 (e = 1): -0.3f = -10066330 * 2^-25, times 2^26 = -20132660 exactly;
+    # next to 3.0 (e = 2) it is -10066330 exactly; next to 5.0 (e = 3) -5033165; next to 9.0 -2516582.5 -> -2516582
+    for big, want in ((1.0, -20132660), (3.0, -10066330), (5.0, -5033165), (9.0, -2516582), (17.0, -1258291)):
+        blk = np.zeros(16, np.float32)
+        blk[0], blk[5] = big, -0.3
+        assert int(o2.quantise(blk, o2.block_exponent(blk))[5]) == want
+
+
+def test_dequantise_two_roundings(o2):
+    """int -> fp32 (round to nearest even), then the power-of-two scaling, which rounds a
+    second time for subnormal results: literal cases where one rounding of the exact value
+    would differ (tests/golden/zc2d_vectors.txt), then random values against numpy."""
+    rows = _golden_2d("D")
+    assert len(rows) == 4
+    for _, q, E, bits in rows:
+        got = o2.dequantise([int(q)] + [0] * 15, int(E))
+        assert "%08x" % int(got[0].view(np.uint32)) == bits, (q, E)
+    rng = np.random.default_rng(57)
+    qs = rng.integers(-(1 << 31), 1 << 31, size=1500)
+    Es = rng.integers(1, 256, size=qs.size)
+    Es[:400] = rng.integers(1, 30, size=400)     # subnormal results
+    with np.errstate(over="ignore"):
+        for q, E in zip(qs, Es):
+            got = o2.dequantise([q] + [0] * 15, int(E))
+            first = np.float64(np.float32(np.int64(q)))
+            want = np.float32(first * 2.0 ** (int(E) - 127 - 27))
+            assert got[0].view(np.uint32) == want.view(np.uint32), (q, E)
+
+
 def _planewise_closed_form(u, ncoef=16):
     out, n = [], 0
     for k in range(31, -1, -1):

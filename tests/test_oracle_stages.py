@@ -109,6 +109,21 @@ def test_dequantise_two_roundings(oracle):
             assert got[3].view(np.uint32) == 0
 
 
+def test_dequantise_double_rounding_literals(oracle):
+    """Cases where rounding the exact value q * 2^(E-155) once differs from what the format
+    says (int -> fp32 first, then the scaling).  With E = 1 the scale is 2^-154, i.e. q/32
+    in units of the smallest subnormal 2^-149.  q = 2^25+17: fp32 spacing in [2^25, 2^26) is
+    4, so float(q) = 2^25+16, and (2^25+16)/32 = 2^20 + 1/2 is a tie that goes to the even
+    2^20 (bits 0x00100000); the exact (2^25+17)/32 = 2^20 + 17/32 would round to 2^20+1.
+    q = 2^26+17: spacing 8, float(q) = 2^26+16, /32 = 2^21 + 1/2 -> 2^21 (exact: 2^21+1).
+    E = 2 halves the divisor: q = 2^25+9 -> float 2^25+8 -> /16 = 2^21 + 1/2 -> 2^21."""
+    for q, E, bits in ((33554449, 1, 0x00100000), (-33554449, 1, 0x80100000),
+                       (67108881, 1, 0x00200000), (-67108881, 1, 0x80200000),
+                       (33554441, 2, 0x00200000), (-33554441, 2, 0x80200000)):
+        got = oracle.dequantise([q, 0, 0, 0], E)
+        assert int(got[0].view(np.uint32)) == bits, (q, E, hex(int(got[0].view(np.uint32))))
+
+
 # ---- stage 3: lifting ----------------------------------------------------------
 
 def test_lift_inverse_exhaustive_small(oracle):
