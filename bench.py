@@ -6,16 +6,22 @@ compressed ring all-reduce performs it (Sec. IV-A):
     zc_compress(local gradients)            fp32 -> stream
     zc_reduce_compressed([incoming, local]) decompress + add + recompress, fused
     zc_decompress(result)                   stream -> fp32
-Workload: the data-parallel gradient bucket (2^28 fp32 values with low-rank
+Headline workload: the data-parallel gradient bucket (2^28 fp32 values with low-rank
 structure, rate 4), synthetic and seeded, resident in HBM before timing starts.
 `value` is GB/s of uncompressed fp32 pushed through the whole step (4*n / step time).
 
-Prints ONE JSON line on stdout.  --sweep adds per-kernel figures for all five
-configurations on stderr (and in the file given with --sweep-out).
+The same JSON line carries, under `configs`, every kernel on all five workloads
+(compress, decompress, 2-way reduce; the ring share as the chain of seven 2-way
+reduces plus the final decompress, and as one 8-way reduce), under `error_per_rate`
+the round-trip error at every rate, and under `copy_GBps` a timed 1 GiB device copy
+(the attainable memory rate on this machine).
+
+Prints ONE JSON line on stdout.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -23,16 +29,37 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
 INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one int32 op per lane-clock
+LLC_BYTES = 256 << 20                       # last-level cache: working sets below this are rotated
 
-# From the rocprofv3 --pmc runs of this same workload summarised under profiles/:
-# HBM bytes per launch (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, the scale a 1 GiB
-# device copy gives on this machine) and wave-level VALU instructions per launch
-# (SQ_INSTS_VALU; x 64 lanes = lane operations).
-# the kernels behind the three calls of the step at rate 4 (names as rocprofv3 prints them)
+HERE = os.path.dirname(os.path.abspath(__file__))
+PROFILE = os.path.join(HERE, "profiles", "zc_rate4_gradient_bucket.md")
+# the kernels behind the three calls of the headline step at rate 4 (names as rocprofv3 prints them)
 KERNEL_NAMES = {"compress": "compress4_wide_kernel<0>", "decompress": "decompress4_wide_kernel<0>",
                 "reduce": "reduce_kernel<4, 4, false, false, 2>"}
-MEASURED_TRAFFIC_BYTES = {"compress": 1208070461, "decompress": 1208412093, "reduce": 402873520}
-MEASURED_VALU_WAVE_INSTS = {"compress": 58195968, "decompress": 11468800, "reduce": 79101952}
+
+
+def profiled_counters(path=PROFILE):
+    """HBM bytes per launch and wave-level VALU instructions per launch of the headline
+    kernels, read from the rocprofv3 summary of this same workload under profiles/
+    (its tables 'Counters' and 'HBM traffic per launch after scaling')."""
+    out = {}
+    try:
+        text = open(path).read()
+    except OSError:
+        return out
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 5 or cells[0] in ("kernel", "---"):
+            continue
+        entry = out.setdefault(cells[0], {})
+        if len(cells) == 6 and re.fullmatch(r"\d+", cells[3] or "") and re.fullmatch(r"\d+", cells[4] or ""):
+            entry["traffic_bytes"] = int(cells[3])          # read MiB | written MiB | total bytes | algorithmic | VALU/block
+        elif len(cells) >= 12:
+            try:
+                entry["valu_wave_insts"] = float(cells[4])   # FETCH | WRITE | WAVES | INSTS_VALU | ...
+            except ValueError:
+                pass
+    return out
 
 
 def algorithmic_bytes(kernel, n, rate, k=2):
@@ -43,15 +70,20 @@ def algorithmic_bytes(kernel, n, rate, k=2):
     return (k + 1) * (n * rate // 8)
 
 
-def time_events(fn, reps, torch):
-    """Per-call durations (ms) measured with HIP events on the launch stream."""
+def time_events(fn, reps, torch, skip=2):
+    """Per-call durations (ms) measured with HIP events on the launch stream;
+    fn gets the iteration number."""
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for a, b in evs:
+    for i, (a, b) in enumerate(evs):
         a.record()
-        fn()
+        fn(i)
         b.record()
     torch.cuda.synchronize()
-    return [a.elapsed_time(b) for a, b in evs]
+    return [a.elapsed_time(b) for a, b in evs][skip:]
+
+
+def frac(nbytes, ms):
+    return round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 
 
 def cpu_baseline(x_host, rate, sample_values, threads):
@@ -75,22 +107,120 @@ def cpu_baseline(x_host, rate, sample_values, threads):
     def run(nthreads):
         bounds = [(n // 4 * i // nthreads) * 4 for i in range(nthreads + 1)]
         parts = [(xs[a:b], peer[a:b]) for a, b in zip(bounds[:-1], bounds[1:])]
-        t0 = time.perf_counter()
         if nthreads == 1:
             inner = [work(parts[0])]
         else:
             with ThreadPoolExecutor(nthreads) as ex:
                 inner = list(ex.map(work, parts))
-        wall = time.perf_counter() - t0
         # the untimed pre-compression of the incoming chunk is excluded via the inner clocks
-        return max(inner), wall
+        return max(inner)
 
-    t1, _ = run(1)
+    t1 = run(1)
     out = {"value": round(4 * n / t1 / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
            "sample": "first %d values of the workload buffer, same three calls as one step" % n}
     if threads > 1:
-        tn, _ = run(threads)
+        tn = run(threads)
         out["all_cores"] = {"value": round(4 * n / tn / 1e9, 4), "cores": threads}
+    return out
+
+
+def error_stats(torch, back, x):
+    err = (back - x).double()
+    return {"max_abs": float("%.4g" % float(err.abs().max())), "rmse": float("%.4g" % float(err.pow(2).mean().sqrt()))}
+
+
+def measure_copy(torch, x, y, reps=8):
+    """A plain device-to-device copy of the 1 GiB buffer: bytes read + written per second."""
+    ms = float(np.median(time_events(lambda i: y.copy_(x), reps, torch)))
+    return round(2 * x.numel() * x.element_size() / (ms * 1e-3) / 1e9, 1)
+
+
+def config_table(torch, zc, workloads, dev, reps=12):
+    """compress / decompress / 2-way reduce on each of the five workloads with the library
+    as it is.  Buffers whose working set would fit the 256 MB last-level cache are rotated
+    through enough copies that every launch reads from and writes to HBM; the ring share is
+    reported both ways and says which."""
+    out = {}
+    for config in (1, 3, 4):
+        rate = workloads.CONFIGS[config]["rate"]
+        entries = {}
+        for label, b in workloads.config_buffers(config):
+            n = b.size
+            per_set = 4 * n + n * rate // 8
+            copies = int(min(96, max(2, np.ceil(1.6 * LLC_BYTES / per_set))))
+            x0 = torch.from_numpy(b).to(dev)
+            xs = [x0] + [x0.clone() for _ in range(copies - 1)]
+            cs = [zc.zc_compress(x, rate) for x in xs]
+            rs = [torch.empty_like(c) for c in cs]
+            ys = [torch.empty_like(x) for x in xs]
+            m = len(xs)
+            tc = time_events(lambda i: zc.zc_compress(xs[i % m], rate, d_out=cs[i % m]), reps + 2, torch)
+            td = time_events(lambda i: zc.zc_decompress(cs[i % m], n, rate, d_out=ys[i % m]), reps + 2, torch)
+            tr = time_events(lambda i: zc.zc_reduce_compressed([cs[i % m], cs[(i + 1) % m]], n, rate, d_out=rs[i % m]),
+                             reps + 2, torch)
+            mc, md, mr = float(np.median(tc)), float(np.median(td)), float(np.median(tr))
+            ab = algorithmic_bytes("compress", n, rate)
+            e = {"n": n, "rate": rate, "rotated_copies": m,
+                 "compress_ms": round(mc, 4), "compress_hbm_frac": frac(ab, mc),
+                 "decompress_ms": round(md, 4), "decompress_hbm_frac": frac(ab, md),
+                 "reduce_k2_ms": round(mr, 4), "reduce_k2_hbm_frac": frac(algorithmic_bytes("reduce", n, rate), mr),
+                 "reduce_k2_uncompressed_GBps": round(4 * n / (mr * 1e-3) / 1e9, 1)}
+            e.update(error_stats(torch, ys[0], xs[0]))
+            if config == 1:
+                # a 4 MiB message is about 1 us of traffic: launch-bound; also as a batch of back-to-back launches
+                t0 = time_events(lambda i: [zc.zc_compress(xs[j], rate, d_out=cs[j]) for j in range(m)], 3, torch, skip=1)
+                t1 = time_events(lambda i: [zc.zc_decompress(cs[j], n, rate, d_out=ys[j]) for j in range(m)], 3, torch, skip=1)
+                e["compress_ms_in_batch"] = round(float(np.median(t0)) / m, 5)
+                e["decompress_ms_in_batch"] = round(float(np.median(t1)) / m, 5)
+                e["note"] = "launch-bound: correctness workload"
+            entries[label] = e
+            del xs, cs, rs, ys, x0
+            torch.cuda.empty_cache()
+        out[str(config)] = entries if len(entries) > 1 else next(iter(entries.values()))
+
+    # the ring share: eight pre-compressed peer chunks
+    rate = workloads.CONFIGS[5]["rate"]
+    bufs = workloads.config_buffers(5)
+    n = bufs[0][1].size
+    comp0 = [zc.zc_compress(torch.from_numpy(b).to(dev), rate) for _, b in bufs]
+    chunk = comp0[0].numel()
+    chain_bytes = 7 * 3 * chunk + chunk + 4 * n
+    k8_bytes = 9 * chunk + chunk + 4 * n
+    share = {"n_per_chunk": n, "rate": rate, "peers": 8}
+    for label, nsets in (("llc_resident", 1), ("rotated", 4)):
+        sets = [comp0] + [[c.clone() for c in comp0] for _ in range(nsets - 1)]
+        accs = [torch.empty_like(comp0[0]) for _ in range(nsets)]
+        finals = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(nsets)]
+
+        def chain(i):
+            comp, acc, final = sets[i % nsets], accs[i % nsets], finals[i % nsets]
+            zc.zc_reduce_compressed([comp[0], comp[1]], n, rate, d_out=acc)
+            for j in range(2, 8):
+                zc.zc_reduce_compressed([acc, comp[j]], n, rate, d_out=acc)   # in place, as a ring hop forwards it
+            zc.zc_decompress(acc, n, rate, d_out=final)
+
+        def direct(i):
+            comp, acc, final = sets[i % nsets], accs[i % nsets], finals[i % nsets]
+            zc.zc_reduce_compressed(comp, n, rate, d_out=acc)
+            zc.zc_decompress(acc, n, rate, d_out=final)
+
+        tch = float(np.median(time_events(chain, reps + 2, torch)))
+        tk8 = float(np.median(time_events(direct, reps + 2, torch)))
+        share[label] = {"chain_7_reduces_plus_decompress_ms": round(tch, 4), "chain_hbm_frac": frac(chain_bytes, tch),
+                        "chain_uncompressed_GBps": round(8 * 4 * n / (tch * 1e-3) / 1e9, 1),
+                        "reduce_k8_plus_decompress_ms": round(tk8, 4), "k8_hbm_frac": frac(k8_bytes, tk8)}
+        if nsets == 1:
+            share[label]["note"] = "16 MiB per chunk: served from the last-level cache, not HBM"
+            chained = finals[0].clone()
+        del sets, accs, finals
+    total = torch.zeros(n, dtype=torch.float64, device=dev)
+    for _, b in bufs:
+        total += torch.from_numpy(b).to(dev).double()
+    err = chained.double() - total
+    share["ring_chain_error_vs_exact_sum"] = {"max_abs": float("%.4g" % float(err.abs().max())),
+                                              "rmse": float("%.4g" % float(err.pow(2).mean().sqrt())),
+                                              "sum_std": float("%.4g" % float(total.std()))}
+    out["5"] = share
     return out
 
 
@@ -100,9 +230,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="leave out the five-workload table and the error per rate")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the ring-hop variants, half precision, 4 x 4 blocks and the lossless codec")
     ap.add_argument("--cpu-sample-log2", type=int, default=26)
-    ap.add_argument("--sweep", action="store_true", help="also time every kernel on all five configurations")
-    ap.add_argument("--sweep-out", default=None, help="file that receives the --sweep figures as JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the 1 GiB input (known traffic, for scaling profiler counters)")
     ap.add_argument("--rates", type=int, nargs="+", default=None,
@@ -177,9 +308,10 @@ def main():
     avg_ms = {nm: float(np.mean([m[i].elapsed_time(m[i + 1]) for m in marks])) for i, nm in enumerate(names)}
     dominant = max(avg_ms, key=avg_ms.get)
     abytes = algorithmic_bytes(dominant, n, rate, k=2)
-    if dominant == "reduce":
+    prof = profiled_counters().get(KERNEL_NAMES[dominant], {})
+    if dominant == "reduce" and "valu_wave_insts" in prof:
         # two decodes and one encode per 6 bytes of traffic: bound by integer VALU work
-        ops = MEASURED_VALU_WAVE_INSTS[dominant] * 64
+        ops = prof["valu_wave_insts"] * 64
         achieved = ops / (avg_ms[dominant] * 1e-3) / 1e12
         roofline = {"kernel": KERNEL_NAMES[dominant], "bound": "alu", "achieved": round(achieved, 2),
                     "peak": round(INT_ALU_PEAK_TOPS, 2), "unit": "Tops/s (int32 lane operations)",
@@ -188,24 +320,84 @@ def main():
         achieved = abytes / (avg_ms[dominant] * 1e-3) / 1e9
         roofline = {"kernel": KERNEL_NAMES[dominant], "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
-    roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_launch_ms": round(avg_ms[dominant], 4),
-                     "algorithmic_bytes": abytes})
+    copy_gbps = measure_copy(torch, x, y)
+    roofline.update({"traffic": prof.get("traffic_bytes"),
+                     "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch from profiles/%s (null if that "
+                                       "summary has no row for this kernel)" % os.path.basename(PROFILE),
+                     "avg_launch_ms": round(avg_ms[dominant], 4), "algorithmic_bytes": abytes,
+                     "frac_of_measured_copy": round(achieved / copy_gbps, 4) if roofline["bound"] == "hbm" else None,
+                     "stream_input": "the 128 MiB stream the decompress kernel reads was written by the reduce kernel just "
+                                     "before it with plain stores, so part of it may come from the 256 MB last-level cache "
+                                     "(at most 11 % of the kernel's bytes); the fp32 side is 1 GiB and comes from / goes to HBM"})
     kernels = {nm: {"avg_ms": round(avg_ms[nm], 4),
                     "uncompressed_GBps": round(4 * n / (avg_ms[nm] * 1e-3) / 1e9, 1),
                     "algorithmic_GBps": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9, 1),
-                    "hbm_frac": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                    "hbm_frac": frac(algorithmic_bytes(nm, n, rate), avg_ms[nm])}
                for nm in names}
 
-    # the two fused ring-hop variants on the same buffers (not part of `value`)
-    hop_mixed = float(np.median(time_events(lambda: zc.zc_reduce_mixed([incoming], x, n, rate, d_out=r), 12, torch)[2:]))
-    hop_raw = float(np.median(time_events(lambda: zc.zc_reduce_decompress([incoming], x, n, rate, d_out=y), 12, torch)[2:]))
+    result = {
+        "metric": "compress/decompress/reduce GB/s (uncompressed fp32) and % of HBM peak",
+        "value": round(4 * n / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
+                               "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
+        "kernels": kernels,
+    }
+    back = zc.zc_decompress(c, n, rate)
+    quality = error_stats(torch, back, x)
+    quality["input_std"] = float("%.4g" % float(x.double().std()))
+    del back
+    if not args.no_extras:
+        result.update(extras(torch, zc, workloads, dev, x, incoming, c, r, y, n, rate))
+    result["round_trip_error"] = quality
+
+    if not args.no_configs:
+        # error of the lossy round trip against the original input at every rate (reported, not a target)
+        per_rate = {}
+        for rr in (4, 8, 12, 16, 20, 24, 28, 32):
+            cc = zc.zc_compress(x, rr)
+            zc.zc_decompress(cc, n, rr, d_out=y)
+            per_rate[str(rr)] = error_stats(torch, y, x)
+            del cc
+        per_rate["data"] = "gradient bucket of configs[1], input std %.4g" % quality["input_std"]
+        result["error_per_rate"] = per_rate
+    del incoming, c
+    torch.cuda.empty_cache()
+    if not args.no_configs:
+        table = config_table(torch, zc, workloads, dev)
+        table["2"] = {"n": n, "rate": rate, "rotated_copies": 1,
+                      "compress_ms": kernels["compress"]["avg_ms"], "compress_hbm_frac": kernels["compress"]["hbm_frac"],
+                      "decompress_ms": kernels["decompress"]["avg_ms"], "decompress_hbm_frac": kernels["decompress"]["hbm_frac"],
+                      "reduce_k2_ms": kernels["reduce"]["avg_ms"], "reduce_k2_hbm_frac": kernels["reduce"]["hbm_frac"],
+                      "max_abs": quality["max_abs"], "rmse": quality["rmse"],
+                      "note": "1 GiB message: no rotation needed; figures from inside the timed step"}
+        result["configs"] = dict(sorted(table.items()))
+    result["copy_GBps"] = copy_gbps
+    result["roofline"] = roofline
+
+    if not args.no_cpu_baseline:
+        del y, r, x
+        torch.cuda.empty_cache()
+        threads = min(16, len(os.sched_getaffinity(0)))
+        result["cpu_baseline"] = cpu_baseline(x_host, rate, 1 << args.cpu_sample_log2, threads)
+    print(json.dumps(result))
+
+
+def extras(torch, zc, workloads, dev, x, incoming, c, r, y, n, rate):
+    """Figures outside `value`, on the headline buffer: the two fused ring-hop variants, the
+    buffer as a bf16 message, 4 x 4 blocks on a matrix of the same size, the lossless codec."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    hop_mixed = float(np.median(time_events(lambda i: zc.zc_reduce_mixed([incoming], x, n, rate, d_out=r), 12, torch)))
+    hop_raw = float(np.median(time_events(lambda i: zc.zc_reduce_decompress([incoming], x, n, rate, d_out=y), 12, torch)))
     mixed_bytes = n * 4 + 2 * (n * rate // 8)
     raw_bytes = 2 * n * 4 + n * rate // 8
-    ring_hop = {"reduce_mixed_ms": round(hop_mixed, 4), "reduce_mixed_hbm_frac": round(mixed_bytes / (hop_mixed * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                "reduce_decompress_ms": round(hop_raw, 4), "reduce_decompress_hbm_frac": round(raw_bytes / (hop_raw * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    ring_hop = {"reduce_mixed_ms": round(hop_mixed, 4), "reduce_mixed_hbm_frac": frac(mixed_bytes, hop_mixed),
+                "reduce_decompress_ms": round(hop_raw, 4), "reduce_decompress_hbm_frac": frac(raw_bytes, hop_raw),
                 "note": "compressed incoming chunk + raw local values -> compressed sum / -> fp32 sum"}
 
-    # the same buffer as a bf16 message (not part of `value`)
+    # the same buffer as a bf16 message
     xh = x.to(torch.bfloat16)
     yh = torch.empty_like(xh)
     ch = torch.empty_like(c)
@@ -223,12 +415,10 @@ def main():
     hc = float(np.median([m[0].elapsed_time(m[1]) for m in half_marks[2:]]))
     hd = float(np.median([m[1].elapsed_time(m[2]) for m in half_marks[2:]]))
     half_precision = {"dtype": "bf16", "compress_ms": round(hc, 4), "decompress_ms": round(hd, 4),
-                      "compress_hbm_frac": round(hb / (hc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                      "decompress_hbm_frac": round(hb / (hd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                      "values_per_s_compress": round(n / (hc * 1e-3), 0)}
-
-    # 4 x 4 blocks on a matrix of the same size and structure (not part of `value`)
+                      "compress_hbm_frac": frac(hb, hc), "decompress_hbm_frac": frac(hb, hd)}
     del xh, yh, ch
+
+    # 4 x 4 blocks on a matrix of the same size and structure
     m_rows, m_cols = 8192, 32768
     xm = torch.from_numpy(workloads.gradient_lowrank(m_rows, m_cols, config=2, index=0)).to(dev).reshape(m_rows, m_cols)
     ym = y.reshape(m_rows, m_cols)
@@ -248,7 +438,7 @@ def main():
         tc = float(np.median([m[0].elapsed_time(m[1]) for m in m2[2:]]))
         td = float(np.median([m[1].elapsed_time(m[2]) for m in m2[2:]]))
         rm = torch.empty_like(cm)
-        tr = float(np.median(time_events(lambda: zc.zc2d_reduce_compressed([cm, cm], m_rows, m_cols, r2, d_out=rm), 12, torch)[2:]))
+        tr = float(np.median(time_events(lambda i: zc.zc2d_reduce_compressed([cm, cm], m_rows, m_cols, r2, d_out=rm), 12, torch)))
         del rm
         mb = 4 * n + cm.numel()
         rel2 = float(((ym - xm).double().pow(2).mean() / xm.double().pow(2).mean()).sqrt())
@@ -257,12 +447,11 @@ def main():
         del one, cm
         blocks_4x4["rate_%d" % r2] = {
             "compress_ms": round(tc, 4), "decompress_ms": round(td, 4), "reduce_2way_ms": round(tr, 4),
-            "compress_hbm_frac": round(mb / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "decompress_hbm_frac": round(mb / (td * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "compress_hbm_frac": frac(mb, tc), "decompress_hbm_frac": frac(mb, td),
             "relative_rms_error": round(rel2, 5), "relative_rms_error_blocks_of_4": round(rel1, 5)}
     del xm, ym
 
-    # the lossless codec on the same buffer, as fp32 words and as a bf16 message (not part of `value`)
+    # the lossless codec on the same buffer, as fp32 words and as a bf16 message
     lossless = {}
     cl = torch.empty(zc.zl_max_compressed_size(n), dtype=torch.uint8, device=dev)
     for label, xl in (("fp32", x), ("bf16", x.to(torch.bfloat16))):
@@ -288,43 +477,11 @@ def main():
         as_int = torch.int16 if half else torch.int32
         lossless[label] = {"stream_over_message": round(size / float(message), 4),
                            "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
-                           "compress_hbm_frac": round(moved / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                           "decompress_hbm_frac": round(moved / (td * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                           "compress_hbm_frac": frac(moved, tc), "decompress_hbm_frac": frac(moved, td),
                            "exact": bool(torch.equal(yl.view(as_int), xl.view(as_int)))}
         del xl, yl
     del cl
-
-    # error of the lossy round trip against the original input (reported, not a target)
-    back = zc.zc_decompress(c, n, rate)
-    err = (back - x).double()
-    quality = {"max_abs_err": float(err.abs().max()), "rmse": float(err.pow(2).mean().sqrt()),
-               "input_std": float(x.double().std())}
-    del back, err
-
-    result = {
-        "metric": "compress/decompress/reduce GB/s (uncompressed fp32) and % of HBM peak",
-        "value": round(4 * n / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
-        "data": "synthetic",
-        "config": {"workload": "configs[1]: DP gradient bucket, 2^28 fp32 (6144x43690 rank-8 + noise), rate 4; "
-                               "step = compress + 2-way fused reduce + decompress", "n_values": n, "rate": rate},
-        "kernels": kernels, "ring_hop": ring_hop, "half_precision": half_precision, "blocks_4x4": blocks_4x4, "lossless": lossless, "roofline": roofline, "round_trip_error": quality,
-    }
-
-    if args.sweep:
-        result_sweep = sweep(torch, zc, workloads, dev)
-        print(json.dumps(result_sweep, indent=1), file=sys.stderr)
-        if args.sweep_out:
-            with open(args.sweep_out, "w") as f:
-                json.dump(result_sweep, f, indent=1)
-
-    if not args.no_cpu_baseline:
-        del y, r
-        torch.cuda.empty_cache()
-        threads = min(16, len(os.sched_getaffinity(0)))
-        result["cpu_baseline"] = cpu_baseline(x_host, rate, 1 << args.cpu_sample_log2, threads)
-    print(json.dumps(result))
+    return {"ring_hop": ring_hop, "half_precision": half_precision, "blocks_4x4": blocks_4x4, "lossless": lossless}
 
 
 def lossless_loop(torch, zc, workloads, dev, reps=12, calibrate=False):
@@ -334,18 +491,17 @@ def lossless_loop(torch, zc, workloads, dev, reps=12, calibrate=False):
     y = torch.empty_like(x)
     zc.zl_compress(x, d_out=c)
     size = zc.zl_stream_bytes(c)
-    tc = time_events(lambda: zc.zl_compress(x, d_out=c), reps, torch)
-    td = time_events(lambda: zc.zl_decompress(c[:size], n, d_out=y), reps, torch)
+    tc = time_events(lambda i: zc.zl_compress(x, d_out=c), reps, torch)
+    td = time_events(lambda i: zc.zl_decompress(c[:size], n, d_out=y), reps, torch)
     if calibrate:
         for _ in range(3):
             y.copy_(x)
         torch.cuda.synchronize()
     moved = 4 * n + size
-    mc, md = float(np.median(tc[2:])), float(np.median(td[2:]))
+    mc, md = float(np.median(tc)), float(np.median(td))
     return {"workload": "configs[1] gradient bucket, 2^28 words", "stream_bytes": size, "stream_over_message": round(size / (4.0 * n), 4),
             "compress_ms": round(mc, 4), "decompress_ms": round(md, 4),
-            "compress_hbm_frac": round(moved / (mc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "decompress_hbm_frac": round(moved / (md * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "compress_hbm_frac": frac(moved, mc), "decompress_hbm_frac": frac(moved, md),
             "exact": bool(torch.equal(y.view(torch.int32), x.view(torch.int32)))}
 
 
@@ -378,76 +534,10 @@ def rate_loop(torch, zc, workloads, dev, rates, reps=12):
         ab = algorithmic_bytes("compress", n, rate)
         out.append({"rate": rate, "data": "gradient bucket" if rate < 16 else "gelu activations",
                     "compress_ms": round(ms[0], 4), "reduce_k2_ms": round(ms[1], 4), "decompress_ms": round(ms[2], 4),
-                    "compress_hbm_frac": round(ab / (ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                    "decompress_hbm_frac": round(ab / (ms[2] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "compress_hbm_frac": frac(ab, ms[0]), "decompress_hbm_frac": frac(ab, ms[2]),
+                    "reduce_hbm_frac": frac(algorithmic_bytes("reduce", n, rate), ms[1]),
                     "reduce_uncompressed_GBps": round(4 * n / (ms[1] * 1e-3) / 1e9, 1)})
         del c, peer, r
-    return out
-
-
-def sweep(torch, zc, workloads, dev):
-    """Per-kernel timings on all five configurations (each buffer rotated through
-    enough copies that the working set exceeds the 256 MB last-level cache)."""
-    out = []
-    for config in (1, 2, 3, 4, 5):
-        rate = workloads.CONFIGS[config]["rate"]
-        bufs = workloads.config_buffers(config)
-        if config == 5:
-            n = bufs[0][1].size
-            comp = [zc.zc_compress(torch.from_numpy(b).to(dev), rate) for _, b in bufs]
-            acc = comp[0].clone()
-            final = torch.empty(n, dtype=torch.float32, device=dev)
-
-            def chain():
-                acc.copy_(comp[0])
-                for j in range(1, 8):
-                    zc.zc_reduce_compressed([acc, comp[j]], n, rate, d_out=acc)
-                zc.zc_decompress(acc, n, rate, d_out=final)
-
-            ms = time_events(chain, 20, torch)[3:]
-            one = time_events(lambda: zc.zc_reduce_compressed([acc, comp[1]], n, rate, d_out=acc), 40, torch)[5:]
-            k8 = time_events(lambda: zc.zc_reduce_compressed(comp, n, rate, d_out=acc), 20, torch)[3:]
-            out.append({"config": 5, "rate": rate, "n": n,
-                        "ring_chain_7_reduces_plus_decompress_ms": float(np.median(ms)),
-                        "reduce_k2_ms": float(np.median(one)),
-                        "reduce_k2_uncompressed_GBps": 4 * n / (float(np.median(one)) * 1e-3) / 1e9,
-                        "reduce_k2_algorithmic_GBps": algorithmic_bytes("reduce", n, rate, 2) / (float(np.median(one)) * 1e-3) / 1e9,
-                        "reduce_k8_ms": float(np.median(k8)),
-                        "reduce_k8_algorithmic_GBps": algorithmic_bytes("reduce", n, rate, 8) / (float(np.median(k8)) * 1e-3) / 1e9,
-                        "note": "working set 16 MiB per chunk: served from the last-level cache, not HBM"})
-            continue
-        for label, b in bufs:
-            n = b.size
-            copies = max(1, int(np.ceil((1 << 29) / (4 * n))))
-            xs = [torch.from_numpy(b).to(dev) for _ in range(min(copies, 8))]
-            cs = [zc.zc_compress(x, rate) for x in xs]
-            ys = [torch.empty_like(x) for x in xs]
-            it = [0]
-
-            def comp_fn():
-                i = it[0] % len(xs)
-                it[0] += 1
-                zc.zc_compress(xs[i], rate, d_out=cs[i])
-
-            def dec_fn():
-                i = it[0] % len(xs)
-                it[0] += 1
-                zc.zc_decompress(cs[i], n, rate, d_out=ys[i])
-
-            tc = float(np.median(time_events(comp_fn, 24, torch)[4:]))
-            td = float(np.median(time_events(dec_fn, 24, torch)[4:]))
-            err = (ys[0] - xs[0]).double()
-            ab = algorithmic_bytes("compress", n, rate)
-            out.append({"config": config, "buffer": label, "rate": rate, "n": n, "rotated_copies": len(xs),
-                        "compress_ms": tc, "decompress_ms": td,
-                        "compress_uncompressed_GBps": 4 * n / (tc * 1e-3) / 1e9,
-                        "decompress_uncompressed_GBps": 4 * n / (td * 1e-3) / 1e9,
-                        "compress_hbm_frac": ab / (tc * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                        "decompress_hbm_frac": ab / (td * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                        "max_abs_err": float(err.abs().max()), "rmse": float(err.pow(2).mean().sqrt()),
-                        "input_std": float(xs[0].double().std())})
-            del xs, cs, ys, err
-            torch.cuda.empty_cache()
     return out
 
 

@@ -5,9 +5,10 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("zc_kernels.hip", "zc2d_kernels.hip", "zl_kernels.hip")]
-DEPS = SOURCES + [os.path.join(HERE, "csrc", f) for f in ("zc_codec.h", "zc2d_codec.h", "zl_codec.h")] + [
+DEPS = SOURCES + [os.path.join(HERE, "csrc", f) for f in ("zc_codec.h", "zc_half.h", "zc2d_codec.h", "zl_codec.h")] + [
                   os.path.join(HERE, "..", "include", "zc.h")]
 LIB = os.path.join(HERE, "libzc.so")
+STAMP = LIB + ".stamp"   # digest of what the library was built from (file times do not survive every copy)
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -19,8 +20,23 @@ FLAGS = [
 ]
 
 
+def deps_digest(extra_flags=()):
+    """Digest of every source, header and compiler flag the library depends on."""
+    import hashlib
+    h = hashlib.sha256(" ".join(FLAGS + list(extra_flags)).encode())
+    for d in DEPS:
+        h.update(os.path.basename(d).encode())
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_stale():
-    return not os.path.exists(LIB) or any(os.path.getmtime(d) > os.path.getmtime(LIB) for d in DEPS)
+    """True if there is no built library or it was built from other sources than the present ones."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
+        return True
+    with open(STAMP) as f:
+        return f.read().strip() != deps_digest()
 
 
 def build(extra_flags=(), out=None):
@@ -41,6 +57,9 @@ def build(extra_flags=(), out=None):
         tmp = out + ".tmp.%d" % os.getpid()
         subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objects + ["-o", tmp])
     os.replace(tmp, out)
+    if out == LIB:
+        with open(STAMP, "w") as f:
+            f.write(deps_digest(extra_flags) + "\n")
     return out
 
 

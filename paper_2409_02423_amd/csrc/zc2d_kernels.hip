@@ -18,8 +18,8 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ const zc2d::ExpandTable g_expand = zc2d::build_expand_table();
-__device__ const zc2d::TokenTable g_token = zc2d::build_token_table();
+__device__ __align__(16) const zc2d::ExpandTable g_expand = zc2d::build_expand_table();
+__device__ __align__(16) const zc2d::TokenTable g_token = zc2d::build_token_table();
 
 // Copy a table of WORDS 32-bit words to LDS, 16 bytes per lane and step.
 template <int WORDS>
@@ -30,7 +30,7 @@ __device__ __forceinline__ void stage_table(const uint32_t* __restrict__ src, ui
   __syncthreads();
 }
 // Workgroups per CU in the grid (measured: the decoder-bound kernels like a few more than
-// the compress kernel).  ZC2D_WORKGROUPS_PER_CU overrides both for tuning runs.
+// the compress kernel).  Only a build with -DZC_TUNING_KNOBS lets ZC2D_WORKGROUPS_PER_CU override both; the shipped library reads no environment variable.
 constexpr int kCompressWorkgroupsPerCU = 16, kDecodeWorkgroupsPerCU = 32;
 
 struct AnyLane {
@@ -322,15 +322,13 @@ int compute_units() {
 }
 
 int workgroups_per_cu(int preset) {
-  static int forced = -1;
-  if (forced < 0) {
-    forced = 0;
-    if (const char* e = getenv("ZC2D_WORKGROUPS_PER_CU")) {
-      const int v = atoi(e);
-      if (v >= 1 && v <= 4096) forced = v;
-    }
+#ifdef ZC_TUNING_KNOBS
+  if (const char* e = getenv("ZC2D_WORKGROUPS_PER_CU")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= 4096) return v;
   }
-  return forced > 0 ? forced : preset;
+#endif
+  return preset;
 }
 
 unsigned grid_for(size_t blocks, int preset) {

@@ -16,9 +16,10 @@
 
 namespace {
 
-__device__ const zc::EncTable g_enc_table = zc::build_enc_table();
-__device__ const zc::DecTable g_dec_table = zc::build_dec_table();
-__device__ const zc::Dec4Table g_dec4_table = zc::build_dec4_table();
+// staged into LDS with 16-byte loads
+__device__ __align__(16) const zc::EncTable g_enc_table = zc::build_enc_table();
+__device__ __align__(16) const zc::DecTable g_dec_table = zc::build_dec_table();
+__device__ __align__(16) const zc::Dec4Table g_dec4_table = zc::build_dec4_table();
 __device__ __align__(16) const zc::Enc4Table g_enc4_table = zc::build_enc4_table();
 
 constexpr int kThreads = 256;          // 4 wavefronts
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (RATE == 4 && c > 0) {
-            zc::accumulate_block4(W[u][0], tab, s[u]);
+            zc::accumulate_block4(W[u][0], tab, s[u], AnyLane());
           } else {
             float y[4];
             zc::decode_block<RATE>(W[u], tab, y, AnyLane());
@@ -545,19 +546,17 @@ int compute_units() {
 // even out the data-dependent coding time, which pays for every coder-bound kernel
 // (measured: 32 to 48 per CU is best at rates 8 and up and for the fused reduce; the
 // wide rate-4 kernels, whose wavefronts take 512 blocks per pass, like 64 and 24).
-// ZC_WORKGROUPS_PER_CU overrides this for tuning runs.
+// The library reads no environment variable; only a build with -DZC_TUNING_KNOBS (never
+// the shipped one) lets ZC_WORKGROUPS_PER_CU override these numbers for tuning runs.
 enum Kernel { kCompress, kDecompress, kReduce };
 
 int workgroups_per_cu(Kernel kernel, int rate) {
-  static int forced = -1;
-  if (forced < 0) {
-    forced = 0;
-    if (const char* e = getenv("ZC_WORKGROUPS_PER_CU")) {
-      int v = atoi(e);
-      if (v >= 1 && v <= 64) forced = v;
-    }
+#ifdef ZC_TUNING_KNOBS
+  if (const char* e = getenv("ZC_WORKGROUPS_PER_CU")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= 64) return v;
   }
-  if (forced > 0) return forced;
+#endif
   switch (kernel) {
     case kCompress: return rate == 4 ? 64 : 32;
     case kDecompress: return rate == 4 ? 24 : 32;

@@ -422,17 +422,16 @@ int compute_units() {
   return cus;
 }
 
-// 256-lane workgroups of the compress kernel per CU (wider workgroups: proportionally fewer); ZL_WORKGROUPS_PER_CU overrides it for tuning runs.
+// 256-lane workgroups of the compress kernel per CU (wider workgroups: proportionally fewer).
+// (Only a build with -DZC_TUNING_KNOBS lets ZL_WORKGROUPS_PER_CU override it.)
 int workgroups_per_cu() {
-  static int forced = -1;
-  if (forced < 0) {
-    forced = 0;
-    if (const char* e = getenv("ZL_WORKGROUPS_PER_CU")) {
-      const int v = atoi(e);
-      if (v >= 1 && v <= 64) forced = v;
-    }
+#ifdef ZC_TUNING_KNOBS
+  if (const char* e = getenv("ZL_WORKGROUPS_PER_CU")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= 64) return v;
   }
-  return forced > 0 ? forced : 4;
+#endif
+  return 4;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -41,10 +41,12 @@ def library_path():
 
 
 def lib():
-    """The loaded C library.  Builds it first only if no built library exists."""
+    """The loaded C library.  Builds it first if there is none or if the one there was built
+    from other sources than the present ones (so a changed kernel is never measured or tested
+    through an old binary); a failed build raises."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if _build.is_stale():
             _build.build()
         L = ctypes.CDLL(_build.LIB)
         L.zc_version.restype = ctypes.c_int

@@ -77,6 +77,46 @@ def test_arbitrary_bytes_decode_alike(gpu, oracle, rate):
     _assert_floats_equal(_host(got), want, "arbitrary bytes rate %d" % rate)
 
 
+@pytest.mark.parametrize("rate", RATES)
+def test_reduce_on_arbitrary_bytes(gpu, oracle, rate):
+    """The three reduce calls on streams of arbitrary bytes (every header byte, every payload):
+    wherever the sum defined by decode-then-add is finite, stream bytes and fp32 sums equal the
+    reference's; where it is infinite the fp32 sum still does (the rate-4 kernel's fused
+    multiply-add must not turn an overflowing decoded value into a finite one); blocks holding
+    a NaN (infinity minus infinity) are only required to be written and repeatable."""
+    print("reduce on arbitrary bytes, rate", rate, flush=True)
+    rng = np.random.default_rng(300 + rate)
+    n = 4 * 20000 + 2
+    size = oracle.compressed_size(n, rate)
+    streams = [rng.integers(0, 256, size=size, dtype=np.uint8) for _ in range(3)]
+    streams[1][: size // 2] &= rng.integers(0, 256, size=size // 2, dtype=np.uint8)
+    # plenty of blocks at the top of the exponent range, where a decoded value overflows
+    for s in streams:
+        hdr = s[:: rate // 2]
+        sel = rng.random(hdr.size) < 0.05
+        hdr[sel] = rng.integers(248, 256, size=int(sel.sum()), dtype=np.uint8)
+    local = workloads.gradient_iid(n) * np.float32(1e30)
+    dstreams = [_dev(s) for s in streams]
+    for k, loc in ((2, None), (3, None), (1, local), (3, local)):
+        with np.errstate(all="ignore"):
+            sums = oracle.reduce_decompress(streams[:k], loc, n, rate)
+            want_c = oracle.reduce_mixed(streams[:k], loc, n, rate)
+        dloc = None if loc is None else _dev(loc)
+        got_raw = _host(gpu.zc_reduce_decompress(dstreams[:k], dloc, n, rate))
+        got_c = _host(gpu.zc_reduce_mixed(dstreams[:k], dloc, n, rate)) if loc is not None else \
+            _host(gpu.zc_reduce_compressed(dstreams[:k], n, rate))
+        again = _host(gpu.zc_reduce_mixed(dstreams[:k], dloc, n, rate))
+        assert np.array_equal(got_c, again)
+        not_nan = ~np.isnan(sums)
+        assert np.isinf(sums).sum() > 50 and (~not_nan).sum() < n // 4
+        _assert_floats_equal(got_raw[not_nan], sums[not_nan], "reduce_decompress arbitrary bytes r%d k%d" % (rate, k))
+        assert np.isnan(got_raw[~not_nan]).all()
+        padded = np.concatenate([sums, np.repeat(sums[-1:], (-n) % 4)]).reshape(-1, 4)
+        finite = np.repeat(np.isfinite(padded).all(axis=1), rate // 2)
+        assert finite.sum() > 0.8 * finite.size
+        _assert_bytes_equal(got_c[finite], want_c[finite], rate // 2, "reduce arbitrary bytes r%d k%d" % (rate, k))
+
+
 @pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
 def test_configs_scaled_down_whole_buffer(gpu, oracle, config):
     """Every configuration's distribution at a size the reference finishes in
