@@ -51,6 +51,23 @@ ZC_DEV uint32_t alignbit(uint32_t hi, uint32_t lo, uint32_t s) {
 #endif
 }
 
+// Byte j of the result is byte sel[j] of the eight bytes {hi, lo} (0..3 = lo, 4..7 = hi);
+// a selector byte of 0x0c gives a zero byte.
+ZC_DEV uint32_t permute_bytes(uint32_t hi, uint32_t lo, uint32_t sel) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_perm(hi, lo, sel);
+#else
+  const uint64_t pool = ((uint64_t)hi << 32) | lo;
+  uint32_t r = 0;
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t c = (sel >> (8 * j)) & 0xFFu;
+    const uint32_t b = c < 8u ? (uint32_t)(pool >> (8u * c)) & 0xFFu : 0u;
+    r |= b << (8 * j);
+  }
+  return r;
+#endif
+}
+
 ZC_DEV uint32_t count_leading_zeros(uint32_t x) { return x ? (uint32_t)__builtin_clz(x) : 32u; }
 ZC_DEV uint32_t count_trailing_zeros(uint32_t x) { return x ? (uint32_t)__builtin_ctz(x) : 32u; }
 ZC_DEV uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
@@ -176,7 +193,10 @@ constexpr Enc4Table build_enc4_table() {
 
 // Decoder, one plane per step.  Index = (n*8 + min(bits left, 7))*128 + next 7 stream
 // bits.  Entry = the plane's bit of coefficient i at bit 8*i | bits consumed << 1 |
-// (next state) << 12, which is the byte offset of that state's 8*128 entries.
+// (next state) << 12, which is the byte offset of that state's 8*128 entries.  With no
+// bits left nothing is read and nothing changes any more, and the entry names state 4 as
+// the next one: "state of at least 3" then also covers "budget spent", which is the one
+// test the decoder's plane loop makes.
 //
 // Behind these, 256 entries for two planes at once when at least three coefficients are
 // significant.  A plane is then four stream bits that are the plane's bits as they are
@@ -193,6 +213,7 @@ constexpr DecTable build_dec_table() {
     for (int avail = 0; avail < 8; ++avail)
       for (int s = 0; s < 128; ++s) {
         PlaneBits r = read_one_plane(n, avail, (uint32_t)s);
+        if (avail == 0) r.next = 4;
         uint32_t spread = (r.p & 1u) | (r.p & 2u) << 7 | (r.p & 4u) << 14 | (r.p & 8u) << 21;
         t.v[(n * 8 + avail) * 128 + s] = spread | (uint32_t)r.used << 1 | (uint32_t)r.next << 12;
       }
@@ -419,6 +440,15 @@ ZC_DEV void inverse_transform(const uint32_t (&u)[4], uint32_t E, float (&out)[4
 }
 
 // W holds the block (bits beyond 4*RATE zero).
+//
+// Rates above 4 decode in two phases.  (1) Planes are read one per step through the table
+// while any lane of the wavefront is still in a state below 3 with bits left; all lanes step
+// together, so the number m of planes read is the same in every lane.  (2) From state 3 on
+// a plane is four stream bits that are the plane's bits as they are (in state 3 the fourth
+// is the group test of the one coefficient left, which is that coefficient's bit), and bits
+// past the budget are zeros in the window and decode as the zeros that unseen bits are; so
+// the rest of the window is taken as it stands, eight planes per 32 bits through the pair
+// table, with no loop, no budget and no state, and joined to the m planes of phase 1.
 template <int RATE, class AnyActive>
 ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab, float (&out)[4],
                          AnyActive any_lane_active) {
@@ -433,9 +463,10 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
 #pragma unroll
     for (int i = 0; i < 4; ++i) out[i] = __builtin_ldexpf(q[i], ex);
   } else {
-    uint32_t u[4];
     constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
     constexpr int kGroups = (kMaxPlanes + 7) / 8;
+    // literal words of phase 2: at least one bit is gone after phase 1, and at most 31 planes remain
+    constexpr int kLiteral = (kPayload - 1 + 31) / 32 < 4 ? (kPayload - 1 + 31) / 32 : 4;
     // leading empty planes = zero bits at the start of the payload
     uint32_t lead = 0;
     {
@@ -451,104 +482,71 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     }
     lead = umin(lead, (uint32_t)kPayload);
     uint32_t left = (uint32_t)kPayload - lead;
-    // a zero block ignores its payload; after 32 empty planes nothing is left to decode
-    if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
     // keep the next stream bit at bit 2 of the window: bits 8..2 index the table directly
     shift_right<NW>(W, lead + 6u);
-    uint32_t state = 0;
-    uint32_t G[kGroups];  // G[g]: byte i = planes 8g..8g+7 (from the top) of coefficient i, first plane in bit 7
+    // a zero block ignores its payload; after 32 empty planes nothing is left to decode
+    if (E == 0u || (kPayload > 32 && lead >= 32u)) {
+      left = 0u;
 #pragma unroll
-    for (int g = 0; g < kGroups; ++g) G[g] = 0;
+      for (int j = 0; j < NW; ++j) W[j] = 0u;
+    }
+    // phase 1.  A[i] collects the planes of coefficient i, the latest in bit 0.
+    uint32_t state = 0, A[4] = {0u, 0u, 0u, 0u};
+    uint32_t m = 0;
     bool open = true;
 #pragma unroll
     for (int g = 0; g < kGroups; ++g) {
       if (open) {
-        if (g > 0 && !any_lane_active(left > 0 && state < 0x3000u)) {
-          // Every lane that still has bits is in state 3 or 4 (which no lane leaves): the
-          // eight planes of this group are the next 32 stream bits, four per plane, as they
-          // are; those past the budget count as zeros.  Looked at between groups only: a
-          // test per plane costs more than it saves at the low rates.
-          uint32_t bits = W[0] >> 2;
-          if constexpr (NW > 1) bits = alignbit(W[1], W[0], 2);
-          const uint32_t len = umin(left, 32u);
-          bits &= len < 32u ? (1u << len) - 1u : 0xFFFFFFFFu;
-          const uint32_t* pair = tab.dec + kDecPlaneEntries;
-          G[g] = pair[bits & 0xFFu] << 6 | pair[(bits >> 8) & 0xFFu] << 4 | pair[(bits >> 16) & 0xFFu] << 2 | pair[bits >> 24];
-          const uint32_t half = umin(len, 16u);
-          shift_out<NW>(W, half);
-          shift_out<NW>(W, len - half);
+        uint32_t acc = 0, mg = 0;   // byte i of acc = this group's planes of coefficient i
+#pragma unroll 1
+        for (; mg < 8u; ++mg) {
+          if (!any_lane_active(state < 0x3000u)) break;
+          const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
+          const uint32_t len = (e >> 1) & 7u;
+          acc = (acc << 1) | (e & 0x01010101u);
+          shift_out<NW>(W, len);
           left -= len;
-          open = any_lane_active(left > 0);
-        } else {
-          uint32_t acc = 0, m = 0;
-          auto one_plane = [&]() {
-            const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
-            const uint32_t len = (e >> 1) & 7u;
-            acc = (acc << 1) | (e & 0x01010101u);
-            shift_out<NW>(W, len);
-            left -= len;
-            state = e & 0x7000u;
-          };
-          if constexpr (RATE < 12) {
-#pragma unroll 1
-            for (; m < 8u; ++m) {
-              if (!any_lane_active(left > 0)) break;
-              one_plane();
-            }
-          } else {
-#pragma unroll 1
-            for (; m < 4u; ++m) {
-              if (!any_lane_active(left > 0)) break;
-              one_plane();
-            }
-            if (m == 4u) {
-              if (!any_lane_active(left > 0 && state < 0x3000u)) {
-                // the same in the middle of a group: its last four planes from 16 stream bits
-                const uint32_t len = umin(left, 16u);
-                const uint32_t bits = (W[0] >> 2) & ((1u << len) - 1u);
-                const uint32_t* pair = tab.dec + kDecPlaneEntries;
-                acc = acc << 4 | pair[bits & 0xFFu] << 2 | pair[bits >> 8];
-                shift_out<NW>(W, len);
-                left -= len;
-                m = 8u;
-              } else {
-#pragma unroll 1
-                for (; m < 6u; ++m) {
-                  if (!any_lane_active(left > 0)) break;
-                  one_plane();
-                }
-                if (m == 6u) {
-                  if (!any_lane_active(left > 0 && state < 0x3000u)) {
-                    // and once more before its last two planes
-                    const uint32_t len = umin(left, 8u);
-                    const uint32_t bits = (W[0] >> 2) & ((1u << len) - 1u);
-                    acc = acc << 2 | tab.dec[kDecPlaneEntries + bits];
-                    shift_out<NW>(W, len);
-                    left -= len;
-                    m = 8u;
-                  } else {
-#pragma unroll 1
-                    for (; m < 8u; ++m) {
-                      if (!any_lane_active(left > 0)) break;
-                      one_plane();
-                    }
-                  }
-                }
-              }
-            }
-          }
-          G[g] = acc << (8u - m);
-          open = m == 8u;
+          state = e & 0x7000u;
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t planes = (acc >> (8 * i)) & 0xFFu;
+          A[i] = g == 0 ? planes : (A[i] << mg) | planes;
+        }
+        m += mg;
+        open = mg == 8u;
+      }
+    }
+    uint32_t u[4];
+    if (m >= 32u) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) u[i] = A[i];
+    } else {
+      // phase 2.  G[j]: byte i = planes m + 8j .. m + 8j + 7 of coefficient i, the first in bit 7
+      const uint32_t* pair = tab.dec + kDecPlaneEntries;
+      uint32_t G[kLiteral];
+#pragma unroll
+      for (int j = 0; j < kLiteral; ++j) {
+        uint32_t bits = W[j] >> 2;
+        if (j + 1 < NW) bits = alignbit(W[j + 1], W[j], 2);
+        G[j] = pair[bits & 0xFFu] << 6 | pair[(bits >> 8) & 0xFFu] << 4 | pair[(bits >> 16) & 0xFFu] << 2 | pair[bits >> 24];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // B = the literal planes of coefficient i from bit 31 down
+        uint32_t B;
+        if constexpr (kLiteral == 1) {
+          B = permute_bytes(0u, G[0], 0x000c0c0cu | (uint32_t)i << 24);
+        } else {
+          B = permute_bytes(G[0], G[1], 0x00000c0cu | (uint32_t)(4 + i) << 24 | (uint32_t)i << 16);
+          if constexpr (kLiteral == 3) B = permute_bytes(B, G[2], 0x0706000cu | (uint32_t)i << 8);
+          if constexpr (kLiteral == 4) B |= permute_bytes(G[2], G[3], 0x0c0c0000u | (uint32_t)(4 + i) << 8 | (uint32_t)i);
+        }
+        u[i] = alignbit(A[i], B, m);   // m is 1..31 here: the m planes of phase 1 above the literal ones
       }
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      uint32_t v = 0;
-#pragma unroll
-      for (int g = 0; g < kGroups; ++g) v |= ((G[g] >> (8 * i)) & 0xFFu) << (24 - 8 * g);
-      u[i] = v >> (lead & 31u);  // nothing was decoded if lead >= 32
-    }
+    for (int i = 0; i < 4; ++i) u[i] >>= (lead & 31u);  // lead >= 32 only in blocks emptied above
     inverse_transform(u, E, out);
   }
 }

@@ -1,7 +1,11 @@
 // Host build of the per-block codec that the GPU kernels run (csrc/zc_codec.h), so
 // that its logic can be checked on the CPU against the reference codec and under
 // host sanitizers before it runs on a GPU.  Test-only: the library never runs this.
+#include <condition_variable>
 #include <cstring>
+#include <mutex>
+#include <thread>
+#include <vector>
 
 #include "../../paper_2409_02423_amd/csrc/zc_codec.h"
 
@@ -29,6 +33,63 @@ void dec(const uint8_t* in, float* x) {
   zc::decode_block<RATE>(W, kTables, o, always);
   std::memcpy(x, o, 16);
 }
+
+// A wavefront on the host: `lanes` threads run the per-lane codec in lockstep, and the
+// wavefront-wide "does any lane ..." of the kernels is a vote among them.  This is how the
+// kernels take their loop decisions, so lanes whose blocks need different numbers of steps
+// are exercised together, as on the GPU.
+struct Ballot {
+  explicit Ballot(int n) : lanes(n) {}
+  bool vote(bool p) {
+    std::unique_lock<std::mutex> lock(mu);
+    any = any || p;
+    if (++arrived == lanes) {
+      result = any;
+      any = false;
+      arrived = 0;
+      ++round;
+      cv.notify_all();
+      return result;
+    }
+    const unsigned long mine = round;
+    cv.wait(lock, [&] { return round != mine; });
+    return result;
+  }
+  std::mutex mu;
+  std::condition_variable cv;
+  int lanes, arrived = 0;
+  bool any = false, result = false;
+  unsigned long round = 0;
+};
+
+template <int RATE>
+void wave(bool encode, const uint8_t* in, size_t blocks, uint8_t* out, int lanes) {
+  constexpr int B = zc::Traits<RATE>::kBlockBytes;
+  Ballot ballot(lanes);
+  auto vote = [&ballot](bool p) { return ballot.vote(p); };
+  const size_t waves = (blocks + lanes - 1) / lanes;
+  std::vector<std::thread> pool;
+  for (int t = 0; t < lanes; ++t)
+    pool.emplace_back([&, t] {
+      for (size_t w = 0; w < waves; ++w) {
+        const size_t j = w * lanes + t;
+        const bool real = j < blocks;   // lanes past the end code a zero block and drop the result
+        if (encode) {
+          uint32_t b[4] = {0, 0, 0, 0}, W[zc::Traits<RATE>::kWords];
+          if (real) std::memcpy(b, in + 16 * j, 16);
+          zc::encode_block<RATE>(b, RATE == 4 ? kTables4 : kTables, W, vote);
+          if (real) std::memcpy(out + j * B, W, B);
+        } else {
+          uint32_t W[zc::Traits<RATE>::kWords] = {};
+          if (real) std::memcpy(W, in + j * B, B);
+          float o[4];
+          zc::decode_block<RATE>(W, kTables, o, vote);
+          if (real) std::memcpy(out + 16 * j, o, 16);
+        }
+      }
+    });
+  for (auto& th : pool) th.join();
+}
 }  // namespace
 
 #define ZC_FOR_RATES(F) F(4) F(8) F(12) F(16) F(20) F(24) F(28) F(32)
@@ -50,5 +111,26 @@ extern "C" int zc_host_decode_blocks(int rate, const uint8_t* in, size_t blocks,
 #undef F
       default: return -2;
     }
+  return 0;
+}
+
+// The same with `lanes` blocks coded in lockstep (see Ballot).
+extern "C" int zc_host_encode_wave(int rate, const float* x, size_t blocks, uint8_t* out, int lanes) {
+  switch (rate) {
+#define F(R) case R: wave<R>(true, reinterpret_cast<const uint8_t*>(x), blocks, out, lanes); break;
+    ZC_FOR_RATES(F)
+#undef F
+    default: return -2;
+  }
+  return 0;
+}
+
+extern "C" int zc_host_decode_wave(int rate, const uint8_t* in, size_t blocks, float* x, int lanes) {
+  switch (rate) {
+#define F(R) case R: wave<R>(false, in, blocks, reinterpret_cast<uint8_t*>(x), lanes); break;
+    ZC_FOR_RATES(F)
+#undef F
+    default: return -2;
+  }
   return 0;
 }

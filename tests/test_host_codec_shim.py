@@ -23,10 +23,12 @@ def shim():
     newest = max(os.path.getmtime(SRC), os.path.getmtime(HDR))
     if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
         subprocess.check_call(["g++", "-std=c++17", "-O2", "-fwrapv", "-ffp-contract=off", "-shared", "-fPIC",
-                               "-fconstexpr-ops-limit=200000000", SRC, "-o", LIB])
+                               "-fconstexpr-ops-limit=200000000", "-pthread", SRC, "-o", LIB])
     L = ctypes.CDLL(LIB)
     L.zc_host_encode_blocks.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.zc_host_decode_blocks.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.zc_host_encode_wave.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int]
+    L.zc_host_decode_wave.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int]
     return L
 
 
@@ -81,3 +83,38 @@ def test_decode_matches_reference(oracle, shim, rate):
         got = _dec(shim, s, 8192, rate)
         bad = np.flatnonzero((got.view(np.uint32) != want.view(np.uint32)).reshape(-1, 4).any(axis=1))
         assert bad.size == 0, (rate, trial, bad[:5])
+
+
+def _mixed_blocks():
+    """Blocks that need very different numbers of coder steps side by side: edge values, constants
+    (one significant coefficient through all planes), zero blocks, ramps, noise, single spikes."""
+    rng = np.random.default_rng(77)
+    parts = [workloads.edge_values(12)[:2048], np.repeat(workloads.gradient_iid(256), 4), np.zeros(256, np.float32),
+             workloads.gradient_iid(2048), (np.arange(1024, dtype=np.float32) * np.float32(1e-3)),
+             workloads.activation_gelu(2048), np.where(rng.random(1024) < 0.1, 1.0, 0.0).astype(np.float32)]
+    blocks = np.concatenate(parts).astype(np.float32).reshape(-1, 4)
+    return blocks[rng.permutation(len(blocks))].reshape(-1)
+
+
+@pytest.mark.parametrize("rate", RATES)
+def test_lockstep_lanes_match_reference(oracle, shim, rate):
+    """The per-lane codec with its wavefront-wide loop decisions taken by a vote among lanes that run
+    in lockstep (16 and 5 lanes): what one lane does must not depend on its neighbours' blocks."""
+    x = _mixed_blocks()[: 4 * 1500]
+    nb = x.size // 4
+    want_c = oracle.compress(x, rate)
+    want_d = oracle.decompress(want_c, x.size, rate)
+    rng = np.random.default_rng(500 + rate)
+    junk = rng.integers(0, 256, size=nb * (rate // 2), dtype=np.uint8)
+    junk[::3] &= rng.integers(0, 256, size=junk[::3].size, dtype=np.uint8)
+    with np.errstate(all="ignore"):
+        want_j = oracle.decompress(junk, x.size, rate)
+    for lanes in (16, 5):
+        got_c = np.zeros_like(want_c)
+        assert shim.zc_host_encode_wave(rate, x.ctypes.data, nb, got_c.ctypes.data, lanes) == 0
+        assert np.array_equal(got_c, want_c), (rate, lanes)
+        for stream, want in ((want_c, want_d), (junk, want_j)):
+            got = np.zeros(x.size, dtype=np.float32)
+            assert shim.zc_host_decode_wave(rate, stream.ctypes.data, nb, got.ctypes.data, lanes) == 0
+            bad = np.flatnonzero((got.view(np.uint32) != want.view(np.uint32)).reshape(-1, 4).any(axis=1))
+            assert bad.size == 0, (rate, lanes, bad[:5])

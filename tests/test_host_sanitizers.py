@@ -21,11 +21,11 @@ def test_reference_and_host_codecs_under_sanitizers():
             objs.append(obj)
         for name in ("zc_codec_host.cpp", "zc2d_codec_host.cpp", "zl_codec_host.cpp", "sanitize_main.cpp"):
             obj = os.path.join(work, name + ".o")
-            subprocess.check_call(["g++", "-std=c++17", "-fwrapv", "-ffp-contract=off", "-fconstexpr-ops-limit=200000000"] + SAN +
+            subprocess.check_call(["g++", "-std=c++17", "-fwrapv", "-ffp-contract=off", "-fconstexpr-ops-limit=200000000", "-pthread"] + SAN +
                                   ["-c", os.path.join(HERE, "shim", name), "-o", obj])
             objs.append(obj)
         exe = os.path.join(work, "sanitize_main")
-        subprocess.check_call(["g++"] + SAN + objs + ["-o", exe, "-lm"])
+        subprocess.check_call(["g++", "-pthread"] + SAN + objs + ["-o", exe, "-lm"])
         env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
         r = subprocess.run([exe], capture_output=True, text=True, timeout=600, env=env)
         assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
