@@ -127,15 +127,14 @@ constexpr PlaneBits read_one_plane(int n, int avail, uint32_t s) {
   return PlaneBits{p, pos, i};
 }
 
-// Encoder, two planes per step.  Index = n*256 + x, where bits 7:6 of x are the next
-// two planes of coefficient 0 (earlier plane in the higher bit), 5:4 of coefficient 1,
-// 3:2 of coefficient 2, 1:0 of coefficient 3.  Entry = code word (bits 13:0) |
-// length << 14 | (byte offset of the next state's 256 entries) << 18.
+// Encoder, two planes per step.  Index = n*256 + x, where the low four bits of x are the
+// earlier plane and the high four bits the later one, bit i of each belonging to coefficient
+// i: a byte of the block's literal plane string (see encode_block).  Entry = code word
+// (bits 13:0) | length << 14 | (byte offset of the next state's 256 entries) << 18.
 //
-// Behind these, 256 entries for eight planes at once when at least three coefficients are
-// significant (a plane is then its four bits as they are, see the decoder's pair table):
-// entry a = the top eight planes of one coefficient, spread so that the plane at bit 7 - p
-// of a lands on stream bit 4*p; coefficient i's entry is shifted up by i.
+// Behind these, 256 entries that turn coefficient words into that literal string: entry a =
+// eight planes of one coefficient, spread so that the plane at bit 7 - p of a lands on bit
+// 4*p; coefficient i's entry is shifted up by i.
 constexpr int kEncPlaneEntries = 5 * 256;
 struct EncTable { uint32_t v[kEncPlaneEntries + 256]; };
 
@@ -143,13 +142,8 @@ constexpr EncTable build_enc_table() {
   EncTable t{};
   for (int n = 0; n <= 4; ++n)
     for (int x = 0; x < 256; ++x) {
-      int first = 0, second = 0;
-      for (int i = 0; i < 4; ++i) {
-        first |= ((x >> (7 - 2 * i)) & 1) << i;
-        second |= ((x >> (6 - 2 * i)) & 1) << i;
-      }
-      PlaneCode a = code_one_plane(n, first);
-      PlaneCode b = code_one_plane(a.next, second);
+      PlaneCode a = code_one_plane(n, x & 15);
+      PlaneCode b = code_one_plane(a.next, x >> 4);
       t.v[n * 256 + x] = (a.code | b.code << a.len) | (uint32_t)(a.len + b.len) << 14 |
                          (uint32_t)(b.next * 256 * 4) << 18;
     }
@@ -277,6 +271,9 @@ struct Tables {
   const float* dec4;
 };
 
+template <int V>
+struct IntConstant { static constexpr int value = V; };
+
 // ---- register window holding one compressed block ----------------------------------
 
 template <int RATE>
@@ -359,18 +356,29 @@ ZC_DEV void forward_transform(const uint32_t (&x)[4], uint32_t& E, uint32_t (&u)
 // Whole block: exponent byte + embedded code of the coefficients, cut at the budget.
 // `any_lane_active(pred)` tells whether any lane of the wavefront still has pred set
 // (loop control only).
+//
+// Rates above 4 encode in two phases, around the block's literal plane string: the planes
+// from the first non-empty one down, four bits each in coefficient order, which is what
+// the stream holds from the moment three coefficients are significant (a plane is then
+// its four bits as they are).  (1) While any lane with bits left is in a state below 3,
+// all lanes code two planes per step through the table, indexed by the next byte of the
+// literal string.  (2) What is left of the budget is filled from the literal string itself:
+// one funnel shift puts the bits of phase 1 and the literal bits behind them in place and
+// cuts at the block's end.  (Planes past plane 0 enter the string as zeros and code as
+// zeros, which is what unused bits are.)
 template <int RATE, class AnyActive>
 ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W)[Traits<RATE>::kWords],
                          AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
+  constexpr int kPayload = Traits<RATE>::kPayloadBits;
   // every plane costs at least one bit, so at most this many planes are ever coded
-  constexpr int kMaxPlanes = Traits<RATE>::kPayloadBits < 32 ? Traits<RATE>::kPayloadBits : 32;
-  constexpr int kMaxSteps = (kMaxPlanes + 1) / 2;
+  constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
+  constexpr int kLitWords = (kMaxPlanes + 7) / 8;
   uint32_t E, u[4];
   forward_transform(x, E, u);
   // leading empty planes: one zero bit each
   const uint32_t lead = count_leading_zeros(u[0] | u[1] | u[2] | u[3]);
-  const int32_t avail = Traits<RATE>::kPayloadBits - (int32_t)lead;
+  const int32_t avail = kPayload - (int32_t)lead;
   uint32_t left = avail > 0 ? (uint32_t)avail : 0u;
 #pragma unroll
   for (int i = 0; i < 4; ++i) u[i] <<= (lead & 31u);  // top plane to bit 31 (all words are zero if lead = 32)
@@ -384,45 +392,80 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
     (void)left;
     (void)any_lane_active;
     return;
-  }
+  } else {
+    // the literal plane string: byte t of it = planes 2t and 2t+1
+    const uint32_t* spread = tab.enc + kEncPlaneEntries;
+    uint32_t lit[kLitWords];
 #pragma unroll
-  for (int j = 0; j < NW; ++j) W[j] = 0;
-  uint32_t state = 0;  // byte offset of the current state's table rows
-#pragma unroll 1
-  for (int step = 0; step < kMaxSteps; ++step) {
-    if (!any_lane_active(left > 0)) break;
-    // Once every lane that still has room is in state 3 or 4 (which no lane leaves), planes
-    // are their four bits as they are: eight planes per step, interleaved by four look-ups.
-    // (Planes past plane 0 come out as zeros, which is what unused bits are.)  Not looked for
-    // at rate 8, whose 24 bits end before it pays, nor in the first four planes.
-    if (RATE >= 12 && step >= 2 && !any_lane_active(left > 0 && state < 3u * 256u * 4u)) {
-      const uint32_t* spread = tab.enc + kEncPlaneEntries;
-      const uint32_t code = spread[u[0] >> 24] | spread[u[1] >> 24] << 1 | spread[u[2] >> 24] << 2 | spread[u[3] >> 24] << 3;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) u[i] <<= 8;
-      const uint32_t first = umin(left, 16u);
-      shift_in<NW>(W, code, first);
-      left -= first;
-      const uint32_t second = umin(left, 16u);
-      shift_in<NW>(W, code >> 16, second);
-      left -= second;
-      continue;
+    for (int j = 0; j < kLitWords; ++j) {
+      const int sh = 24 - 8 * j;
+      lit[j] = spread[(u[0] >> sh) & 0xFFu] | spread[(u[1] >> sh) & 0xFFu] << 1 | spread[(u[2] >> sh) & 0xFFu] << 2 |
+               spread[(u[3] >> sh) & 0xFFu] << 3;
     }
-    uint32_t idx = u[0] >> 30;
-    idx = alignbit(idx, u[1], 30);  // (idx << 2) | top two bits of the next word
-    idx = alignbit(idx, u[2], 30);
-    idx = alignbit(idx, u[3], 30);
+    // phase 1: code words enter at the top of the window P, older bits move down
+    uint32_t P[NW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) u[i] <<= 2;
-    const uint32_t e = tab.enc[(state >> 2) + idx];
-    const uint32_t len = umin((e >> 14) & 15u, left);
-    shift_in<NW>(W, e, len);  // only the low `len` bits of e enter the window
-    left -= len;
-    state = e >> 18;
+    for (int j = 0; j < NW; ++j) P[j] = 0;
+    uint32_t state = 0;   // byte offset of the current state's table rows
+    uint32_t steps = 0;   // the same in every lane
+    bool open = true;
+#pragma unroll
+    for (int w = 0; w < kLitWords; ++w) {
+      if (open) {
+        uint32_t z = lit[w], s = 0;
+#pragma unroll 1
+        for (; s < 4u; ++s) {
+          if (!any_lane_active(left > 0 && state < 3u * 256u * 4u)) break;
+          const uint32_t e = tab.enc[(state >> 2) + (z & 0xFFu)];
+          z >>= 8;
+          const uint32_t len = umin((e >> 14) & 15u, left);
+          shift_in<NW>(P, e, len);  // only the low `len` bits of e enter the window
+          left -= len;
+          state = e >> 18;
+        }
+        steps += s;
+        open = s == 4u;
+      }
+    }
+    // phase 2: X = the window of phase 1 with the literal string from byte `steps` on above it
+    uint32_t X[2 * NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) X[j] = P[j];
+    const uint32_t byte_shift = 8u * (steps & 3u);
+    auto literal_from = [&](auto first_word) {
+      constexpr int w0 = decltype(first_word)::value;
+#pragma unroll
+      for (int j = 0; j < NW; ++j) {
+        const uint32_t lo = w0 + j < kLitWords ? lit[w0 + j < kLitWords ? w0 + j : 0] : 0u;
+        const uint32_t hi = w0 + j + 1 < kLitWords ? lit[w0 + j + 1 < kLitWords ? w0 + j + 1 : 0] : 0u;
+        X[NW + j] = alignbit(hi, lo, byte_shift);
+      }
+    };
+    switch (steps >> 2) {
+      case 0: literal_from(IntConstant<0>()); break;
+      case 1: literal_from(IntConstant<1>()); break;
+      case 2: literal_from(IntConstant<2>()); break;
+      case 3: literal_from(IntConstant<3>()); break;
+      default: literal_from(IntConstant<4>()); break;
+    }
+    // the coded bits of phase 1 sit at the top of P and the first of them belongs at bit
+    // 8 + lead: everything moves down by the unused budget (and by the window's excess
+    // over the block), which brings exactly `left` literal bits into the block
+    const uint32_t down = (uint32_t)(32 * NW - Traits<RATE>::kBlockBits) + left;
+    const uint32_t r = down & 31u, k = down >> 5;
+    uint32_t F[2 * NW - 1];
+#pragma unroll
+    for (int j = 0; j < 2 * NW - 1; ++j) F[j] = alignbit(X[j + 1], X[j], r);
+#pragma unroll
+    for (int o = 0; o < NW; ++o) {
+      uint32_t v = F[o];
+#pragma unroll
+      for (int d = 1; d < NW; ++d) v = (k == (uint32_t)d) ? F[o + d] : v;
+      W[o] = v;
+    }
+    if constexpr (Traits<RATE>::kBlockBits % 32 != 0) W[NW - 1] &= (1u << (Traits<RATE>::kBlockBits % 32)) - 1u;
+    W[0] |= E;
   }
-  // the coded bits sit at the top of the window; the first belongs at bit 8 + lead
-  shift_right<NW>(W, (uint32_t)(32 * NW - Traits<RATE>::kBlockBits) + left);
-  W[0] |= E;
 }
 
 // ---- inverse path ------------------------------------------------------------------

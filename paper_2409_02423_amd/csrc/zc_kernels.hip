@@ -172,23 +172,30 @@ __device__ __forceinline__ void load_stream(const uint8_t* in, size_t j, uint32_
   }
 }
 
-template <int RATE>
+// NT: non-temporal stores (the compress kernels: their stream is read next by another
+// device or a later kernel, and not keeping it in the caches made them 6 to 8 % faster);
+// plain stores otherwise (the fused reduce, whose output the next hop reads at once).
+template <int RATE, bool NT = false>
 __device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint32_t (&W)[zc::Traits<RATE>::kWords]) {
   constexpr int B = zc::Traits<RATE>::kBlockBytes;
   uint8_t* p = out + j * B;
+  auto put = [](auto* q, auto v) {
+    if constexpr (NT) nt_store(q, v);
+    else stream_store(q, v);
+  };
   if constexpr (B == 16) {
     u32x4 v = {W[0], W[1], W[2], W[3]};
-    stream_store(reinterpret_cast<u32x4*>(p), v);
+    put(reinterpret_cast<u32x4*>(p), v);
   } else if constexpr (B == 8) {
     u32x2 v = {W[0], W[1]};
-    stream_store(reinterpret_cast<u32x2*>(p), v);
+    put(reinterpret_cast<u32x2*>(p), v);
   } else if constexpr (B % 4 == 0) {
 #pragma unroll
-    for (int i = 0; i < B / 4; ++i) stream_store(reinterpret_cast<uint32_t*>(p) + i, W[i]);
+    for (int i = 0; i < B / 4; ++i) put(reinterpret_cast<uint32_t*>(p) + i, W[i]);
   } else {
     uint16_t* h = reinterpret_cast<uint16_t*>(p);
 #pragma unroll
-    for (int i = 0; i < B / 2; ++i) stream_store(h + i, (uint16_t)(W[i / 2] >> (16 * (i % 2))));
+    for (int i = 0; i < B / 2; ++i) put(h + i, (uint16_t)(W[i / 2] >> (16 * (i % 2))));
   }
 }
 
@@ -196,9 +203,10 @@ __device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint3
 // Work is cut into tiles of U * 256 consecutive blocks; a workgroup takes tiles with a
 // grid stride and lane t codes blocks t, t + 256, ... of the tile, so every access of
 // a wavefront is one contiguous span.  All U loads of the next tile are issued before
-// the current tile is coded (always from an in-bounds address, so no branch surrounds
-// them): that keeps U accesses per lane in flight, which is what the narrow stream
-// accesses (RATE/2 bytes per lane) need to cover memory latency.  Blocks after the
+// the current tile is coded (under a test that is the same for the whole workgroup; a
+// workgroup's last tile fetches nothing more): that keeps U accesses per lane in flight,
+// which is what the narrow stream accesses (RATE/2 bytes per lane) need to cover memory
+// latency.  Blocks after the
 // last whole tile are coded one per lane, and the ragged last block (n % 4 values) by
 // a single lane.
 
@@ -227,16 +235,17 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restri
     for (int u = 0; u < U; ++u) load_values<DT>(in, t * kTile + u * kThreads + threadIdx.x, x[u]);
     while (true) {
       const size_t tn = t + gridDim.x;
-      const bool more = tn < tiles;
-      const size_t next = (more ? tn : t) * kTile + threadIdx.x;
+      const bool more = tn < tiles;   // the same in every lane of the workgroup
       uint32_t xn[U][4];
+      if (more) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) load_values<DT>(in, next + u * kThreads, xn[u]);
+        for (int u = 0; u < U; ++u) load_values<DT>(in, tn * kTile + u * kThreads + threadIdx.x, xn[u]);
+      }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         uint32_t W[NW];
         zc::encode_block<RATE>(x[u], tab, W, AnyLane());
-        store_stream<RATE>(out, t * kTile + u * kThreads + threadIdx.x, W);
+        store_stream<RATE, true>(out, t * kTile + u * kThreads + threadIdx.x, W);
       }
       if (!more) break;
 #pragma unroll
@@ -251,13 +260,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restri
     uint32_t x[4], W[NW];
     load_values<DT>(in, j, x);
     zc::encode_block<RATE>(x, tab, W, AnyLane());
-    store_stream<RATE>(out, j, W);
+    store_stream<RATE, true>(out, j, W);
   }
   if ((n & 3) != 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     uint32_t x[4], W[NW];
     load_values_ragged<DT>(in, n, x);
     zc::encode_block<RATE>(x, tab, W, AnyLane());
-    store_stream<RATE>(out, whole, W);
+    store_stream<RATE, true>(out, whole, W);
   }
 }
 
@@ -278,11 +287,12 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
     for (int u = 0; u < U; ++u) load_stream<RATE>(in, t * kTile + u * kThreads + threadIdx.x, W[u]);
     while (true) {
       const size_t tn = t + gridDim.x;
-      const bool more = tn < tiles;
-      const size_t next = (more ? tn : t) * kTile + threadIdx.x;
+      const bool more = tn < tiles;   // the same in every lane of the workgroup
       uint32_t Wn[U][NW];
+      if (more) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) load_stream<RATE>(in, next + u * kThreads, Wn[u]);
+        for (int u = 0; u < U; ++u) load_stream<RATE>(in, tn * kTile + u * kThreads + threadIdx.x, Wn[u]);
+      }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         float y[4];
@@ -459,10 +469,12 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
       for (int c = 0; c < k; ++c) {
         const bool last = c + 1 == k;
         const uint8_t* src = chunks.p[last ? 0 : c + 1];
-        const size_t next = (last ? (more ? tn : t) : t) * kTile + threadIdx.x;
+        const size_t next = (last ? tn : t) * kTile + threadIdx.x;
         uint32_t Wn[U][NW];
+        if (!last || more) {   // after the last chunk of the last tile there is nothing to fetch
 #pragma unroll
-        for (int u = 0; u < U; ++u) load_stream<RATE>(src, next + u * kThreads, Wn[u]);
+          for (int u = 0; u < U; ++u) load_stream<RATE>(src, next + u * kThreads, Wn[u]);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (RATE == 4 && c > 0) {
@@ -473,8 +485,10 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 #pragma unroll
             for (int i = 0; i < 4; ++i) s[u][i] = c ? s[u][i] + y[i] : y[i];
           }
+          if (!last || more) {
 #pragma unroll
-          for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
+            for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
+          }
         }
       }
 #pragma unroll
