@@ -70,13 +70,27 @@ def algorithmic_bytes(kernel, n, rate, k=2):
     return (k + 1) * (n * rate // 8)
 
 
-def time_events(fn, reps, torch, skip=2):
-    """Per-call durations (ms) measured with HIP events on the launch stream;
-    fn gets the iteration number."""
+SETTLE_MS = 60.0   # untimed launches before a kernel is timed on its own (see time_events)
+
+
+def time_events(fn, reps, torch, skip=0, settle_ms=SETTLE_MS):
+    """Per-call durations (ms) measured with HIP events on the launch stream; fn gets the
+    iteration number.  Before timing, fn is launched untimed for `settle_ms` of wall time:
+    back-to-back launches of one kernel go through a clock transient on this GPU (the same
+    launch takes up to 40 % longer between about 3 and 15 ms after the load starts, then
+    settles), so a kernel timed on its own is timed in its settled state."""
+    i = 0
+    t0 = time.perf_counter()
+    while settle_ms > 0 and (time.perf_counter() - t0) * 1e3 < settle_ms:
+        for _ in range(10):
+            fn(i)
+            i += 1
+        torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for i, (a, b) in enumerate(evs):
+    for a, b in evs:
         a.record()
         fn(i)
+        i += 1
         b.record()
     torch.cuda.synchronize()
     return [a.elapsed_time(b) for a, b in evs][skip:]
@@ -135,7 +149,7 @@ def measure_copy(torch, x, y, reps=8):
     return round(2 * x.numel() * x.element_size() / (ms * 1e-3) / 1e9, 1)
 
 
-def config_table(torch, zc, workloads, dev, reps=12):
+def config_table(torch, zc, workloads, dev, reps=20):
     """compress / decompress / 2-way reduce on each of the five workloads with the library
     as it is.  Buffers whose working set would fit the 256 MB last-level cache are rotated
     through enough copies that every launch reads from and writes to HBM; the ring share is
@@ -154,10 +168,10 @@ def config_table(torch, zc, workloads, dev, reps=12):
             rs = [torch.empty_like(c) for c in cs]
             ys = [torch.empty_like(x) for x in xs]
             m = len(xs)
-            tc = time_events(lambda i: zc.zc_compress(xs[i % m], rate, d_out=cs[i % m]), reps + 2, torch)
-            td = time_events(lambda i: zc.zc_decompress(cs[i % m], n, rate, d_out=ys[i % m]), reps + 2, torch)
+            tc = time_events(lambda i: zc.zc_compress(xs[i % m], rate, d_out=cs[i % m]), reps, torch)
+            td = time_events(lambda i: zc.zc_decompress(cs[i % m], n, rate, d_out=ys[i % m]), reps, torch)
             tr = time_events(lambda i: zc.zc_reduce_compressed([cs[i % m], cs[(i + 1) % m]], n, rate, d_out=rs[i % m]),
-                             reps + 2, torch)
+                             reps, torch)
             mc, md, mr = float(np.median(tc)), float(np.median(td)), float(np.median(tr))
             ab = algorithmic_bytes("compress", n, rate)
             e = {"n": n, "rate": rate, "rotated_copies": m,
@@ -168,8 +182,8 @@ def config_table(torch, zc, workloads, dev, reps=12):
             e.update(error_stats(torch, ys[0], xs[0]))
             if config == 1:
                 # a 4 MiB message is about 1 us of traffic: launch-bound; also as a batch of back-to-back launches
-                t0 = time_events(lambda i: [zc.zc_compress(xs[j], rate, d_out=cs[j]) for j in range(m)], 3, torch, skip=1)
-                t1 = time_events(lambda i: [zc.zc_decompress(cs[j], n, rate, d_out=ys[j]) for j in range(m)], 3, torch, skip=1)
+                t0 = time_events(lambda i: [zc.zc_compress(xs[j], rate, d_out=cs[j]) for j in range(m)], 3, torch)
+                t1 = time_events(lambda i: [zc.zc_decompress(cs[j], n, rate, d_out=ys[j]) for j in range(m)], 3, torch)
                 e["compress_ms_in_batch"] = round(float(np.median(t0)) / m, 5)
                 e["decompress_ms_in_batch"] = round(float(np.median(t1)) / m, 5)
                 e["note"] = "launch-bound: correctness workload"
@@ -204,8 +218,8 @@ def config_table(torch, zc, workloads, dev, reps=12):
             zc.zc_reduce_compressed(comp, n, rate, d_out=acc)
             zc.zc_decompress(acc, n, rate, d_out=final)
 
-        tch = float(np.median(time_events(chain, reps + 2, torch)))
-        tk8 = float(np.median(time_events(direct, reps + 2, torch)))
+        tch = float(np.median(time_events(chain, reps, torch)))
+        tk8 = float(np.median(time_events(direct, reps, torch)))
         share[label] = {"chain_7_reduces_plus_decompress_ms": round(tch, 4), "chain_hbm_frac": frac(chain_bytes, tch),
                         "chain_uncompressed_GBps": round(8 * 4 * n / (tch * 1e-3) / 1e9, 1),
                         "reduce_k8_plus_decompress_ms": round(tk8, 4), "k8_hbm_frac": frac(k8_bytes, tk8)}
@@ -290,6 +304,11 @@ def main():
             e[3].record()
             marks.append(e)
 
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < SETTLE_MS:   # settle the clocks (untimed, see time_events)
+        for _ in range(5):
+            step(False)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -518,6 +537,13 @@ def rate_loop(torch, zc, workloads, dev, rates, reps=12):
         c = zc.zc_compress(x, rate)
         peer = zc.zc_compress(torch.flip(x, [0]).contiguous(), rate)
         r = torch.empty_like(c)
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < SETTLE_MS:   # settle the clocks (untimed, see time_events)
+            for _ in range(5):
+                zc.zc_compress(x, rate, d_out=c)
+                zc.zc_reduce_compressed([peer, c], n, rate, d_out=r)
+                zc.zc_decompress(r, n, rate, d_out=y)
+            torch.cuda.synchronize()
         marks = []
         for _ in range(reps):
             e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -530,7 +556,7 @@ def rate_loop(torch, zc, workloads, dev, rates, reps=12):
             e[3].record()
             marks.append(e)
         torch.cuda.synchronize()
-        ms = [float(np.median([m[i].elapsed_time(m[i + 1]) for m in marks[2:]])) for i in range(3)]
+        ms = [float(np.median([m[i].elapsed_time(m[i + 1]) for m in marks])) for i in range(3)]
         ab = algorithmic_bytes("compress", n, rate)
         out.append({"rate": rate, "data": "gradient bucket" if rate < 16 else "gelu activations",
                     "compress_ms": round(ms[0], 4), "reduce_k2_ms": round(ms[1], 4), "decompress_ms": round(ms[2], 4),

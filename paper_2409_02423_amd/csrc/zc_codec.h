@@ -595,26 +595,29 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
 }
 
 // Rate 4: sum += the decoded block, with one rounding per value as a decode followed by an
-// add would give: the table's entries are integers below 2^9 and 2^(E - 133) is a
-// representable (possibly subnormal) power of two, so their product is exact and the fused
+// add would give.  Fused form: the table's entries are integers below 2^9 and 2^(E - 133) is
+// a representable (possibly subnormal) power of two, so their product is exact and the fused
 // multiply-add rounds the same sum once.  That holds while the product is finite; from
 // E = 252 on it may overflow (only arbitrary bytes or values of 2^127 and more produce such
-// an exponent), where a decoded infinity plus the sum is not what the fused form gives, so a
-// wavefront in which any lane has E >= 250 decodes and adds in two steps.
-template <class AnyActive>
-ZC_DEV void accumulate_block4(uint32_t W0, const Tables& tab, float (&sum)[4], AnyActive any_lane_active) {
+// an exponent), where a decoded infinity plus the sum is not what the fused form gives: the
+// caller then asks for the two-step form (see may_overflow4).
+template <bool TWO_STEPS>
+ZC_DEV void accumulate_block4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
   const uint32_t E = W0 & 0xFFu;
   const float* q = tab.dec4 + 4u * (E ? W0 >> 8 : 0u);
   const int ex = (int)E - 127 - kFractionBits + 22;
-  if (any_lane_active(E >= 250u)) {
+  if constexpr (TWO_STEPS) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) sum[i] = sum[i] + __builtin_ldexpf(q[i], ex);
-    return;
-  }
-  const float scale = __builtin_ldexpf(1.0f, ex);
+  } else {
+    const float scale = __builtin_ldexpf(1.0f, ex);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) sum[i] = __builtin_fmaf(q[i], scale, sum[i]);
+    for (int i = 0; i < 4; ++i) sum[i] = __builtin_fmaf(q[i], scale, sum[i]);
+  }
 }
+
+// Whether a rate-4 block's exponent byte is high enough for a decoded value to overflow.
+ZC_DEV bool may_overflow4(uint32_t W0) { return (W0 & 0xFFu) >= 250u; }
 
 }  // namespace zc
 #endif  // ZC_CODEC_H

@@ -475,20 +475,33 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 #pragma unroll
           for (int u = 0; u < U; ++u) load_stream<RATE>(src, next + u * kThreads, Wn[u]);
         }
+        if (RATE == 4 && c > 0) {
+          // rate 4, chunks after the first: fused multiply-add, unless some block of this tile in
+          // some lane of the wavefront has an exponent byte at which a decoded value overflows
+          bool high = false;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (RATE == 4 && c > 0) {
-            zc::accumulate_block4(W[u][0], tab, s[u], AnyLane());
+          for (int u = 0; u < U; ++u) high = high || zc::may_overflow4(W[u][0]);
+          if (AnyLane()(high)) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) zc::accumulate_block4<true>(W[u][0], tab, s[u]);
           } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) zc::accumulate_block4<false>(W[u][0], tab, s[u]);
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
             float y[4];
             zc::decode_block<RATE>(W[u], tab, y, AnyLane());
 #pragma unroll
             for (int i = 0; i < 4; ++i) s[u][i] = c ? s[u][i] + y[i] : y[i];
           }
-          if (!last || more) {
+        }
+        if (!last || more) {
+#pragma unroll
+          for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
-          }
         }
       }
 #pragma unroll
