@@ -335,7 +335,18 @@ ZC_DEV void shift_out(uint32_t (&W)[NW], uint32_t len) {
 // scaling is exact in fp32 (a result below 2^-126 may round, but truncates to 0 either
 // way) and the float -> int conversion truncates.
 ZC_DEV void forward_transform(const uint32_t (&x)[4], uint32_t& E, uint32_t (&u)[4]) {
-  uint32_t m = umax(umax(x[0] & 0x7FFFFFFFu, x[1] & 0x7FFFFFFFu), umax(x[2] & 0x7FFFFFFFu, x[3] & 0x7FFFFFFFu));
+  // largest magnitude as a bit pattern
+#if defined(__HIP_DEVICE_COMPILE__)
+  // For finite values the float maximum of the magnitudes is the same pattern as the integer
+  // maximum of the patterns without their sign bits; the instructions take |x| as an operand
+  // modifier (subnormals are kept: the kernels run with fp32 denormals on).
+  float m3, mf;
+  asm("v_max3_f32 %0, |%1|, |%2|, |%3|" : "=v"(m3) : "v"(bits_to_float(x[0])), "v"(bits_to_float(x[1])), "v"(bits_to_float(x[2])));
+  asm("v_max_f32_e64 %0, |%1|, |%2|" : "=v"(mf) : "v"(m3), "v"(bits_to_float(x[3])));
+  const uint32_t m = __builtin_bit_cast(uint32_t, mf);
+#else
+  const uint32_t m = umax(umax(x[0] & 0x7FFFFFFFu, x[1] & 0x7FFFFFFFu), umax(x[2] & 0x7FFFFFFFu, x[3] & 0x7FFFFFFFu));
+#endif
   E = (m >> 23) + (m != 0u ? 1u : 0u);
   const int scale = 127 + kFractionBits - (int)E;
   int32_t a = (int32_t)__builtin_ldexpf(bits_to_float(x[0]), scale);
@@ -393,25 +404,34 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
     (void)any_lane_active;
     return;
   } else {
-    // the literal plane string: byte t of it = planes 2t and 2t+1
+    // the literal plane string: byte t of it = planes 2t and 2t+1.  Its words are made when they
+    // are first needed: word 0 now, a later word when phase 1 reaches it or when some lane's
+    // remaining budget reaches into it.
     const uint32_t* spread = tab.enc + kEncPlaneEntries;
     uint32_t lit[kLitWords];
-#pragma unroll
-    for (int j = 0; j < kLitWords; ++j) {
+    auto make_word = [&](int j) {
       const int sh = 24 - 8 * j;
       lit[j] = spread[(u[0] >> sh) & 0xFFu] | spread[(u[1] >> sh) & 0xFFu] << 1 | spread[(u[2] >> sh) & 0xFFu] << 2 |
                spread[(u[3] >> sh) & 0xFFu] << 3;
-    }
+    };
+    make_word(0);
+#pragma unroll
+    for (int j = 1; j < kLitWords; ++j) lit[j] = 0u;
     // phase 1: code words enter at the top of the window P, older bits move down
     uint32_t P[NW];
 #pragma unroll
     for (int j = 0; j < NW; ++j) P[j] = 0;
     uint32_t state = 0;   // byte offset of the current state's table rows
     uint32_t steps = 0;   // the same in every lane
+    int made = 1;         // words of the literal string made so far (the same in every lane)
     bool open = true;
 #pragma unroll
     for (int w = 0; w < kLitWords; ++w) {
       if (open) {
+        if (w > 0 && any_lane_active(left > 0 && state < 3u * 256u * 4u)) {
+          make_word(w);
+          made = w + 1;
+        }
         uint32_t z = lit[w], s = 0;
 #pragma unroll 1
         for (; s < 4u; ++s) {
@@ -425,6 +445,17 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
         }
         steps += s;
         open = s == 4u;
+      }
+    }
+    // word j of the string is needed below iff some lane's budget reaches past bit 32*j of it
+    {
+      bool further = true;
+#pragma unroll
+      for (int j = 1; j < kLitWords; ++j) {
+        if (further) {
+          further = any_lane_active(left + 8u * steps > 32u * (uint32_t)j);
+          if (further && j >= made) make_word(j);
+        }
       }
     }
     // phase 2: X = the window of phase 1 with the literal string from byte `steps` on above it
@@ -470,8 +501,20 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
 
 // ---- inverse path ------------------------------------------------------------------
 
+// (u xor 0xAAAAAAAA) - 0xAAAAAAAA; on the device one xor-add instruction (its two constants
+// cannot both be immediates, so one sits in a scalar and one in a vector register).
+ZC_DEV int32_t negabinary_to_int(uint32_t u) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  uint32_t r;
+  asm("v_xad_u32 %0, %1, %2, %3" : "=v"(r) : "v"(u), "s"(0xAAAAAAAAu), "v"(0x55555556u));
+  return (int32_t)r;
+#else
+  return from_negabinary(u);
+#endif
+}
+
 ZC_DEV void inverse_transform(const uint32_t (&u)[4], uint32_t E, float (&out)[4]) {
-  int32_t a = from_negabinary(u[0]), b = from_negabinary(u[1]), c = from_negabinary(u[2]), d = from_negabinary(u[3]);
+  int32_t a = negabinary_to_int(u[0]), b = negabinary_to_int(u[1]), c = negabinary_to_int(u[2]), d = negabinary_to_int(u[3]);
   inverse_lift(a, b, c, d);
   const int ex = (int)E - 127 - kFractionBits;
   // int -> fp32 rounds to nearest even; the scaling is exact and rounds once more only
@@ -530,6 +573,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     // a zero block ignores its payload; after 32 empty planes nothing is left to decode
     if (E == 0u || (kPayload > 32 && lead >= 32u)) {
       left = 0u;
+      lead = 0u;
 #pragma unroll
       for (int j = 0; j < NW; ++j) W[j] = 0u;
     }
@@ -544,7 +588,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
 #pragma unroll 1
         for (; mg < 8u; ++mg) {
           if (!any_lane_active(state < 0x3000u)) break;
-          const uint32_t e = tab.dec[(state | umin(left, 7u) << 9 | (W[0] & 0x1FCu)) >> 2];
+          const uint32_t e = tab.dec[(umin(left, 7u) << 9 | ((W[0] & 0x1FCu) | state)) >> 2];
           const uint32_t len = (e >> 1) & 7u;
           acc = (acc << 1) | (e & 0x01010101u);
           shift_out<NW>(W, len);
@@ -563,7 +607,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     uint32_t u[4];
     if (m >= 32u) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) u[i] = A[i];
+      for (int i = 0; i < 4; ++i) u[i] = A[i] >> lead;   // lead is below 32 (blocks with more were emptied above)
     } else {
       // phase 2.  G[j]: byte i = planes m + 8j .. m + 8j + 7 of coefficient i, the first in bit 7
       const uint32_t* pair = tab.dec + kDecPlaneEntries;
@@ -585,11 +629,19 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
           if constexpr (kLiteral == 3) B = permute_bytes(B, G[2], 0x0706000cu | (uint32_t)i << 8);
           if constexpr (kLiteral == 4) B |= permute_bytes(G[2], G[3], 0x0c0c0000u | (uint32_t)(4 + i) << 8 | (uint32_t)i);
         }
-        u[i] = alignbit(A[i], B, m);   // m is 1..31 here: the m planes of phase 1 above the literal ones
+        u[i] = B;
+      }
+      // the m planes of phase 1 (m is 1..31 here) above the literal ones, and all of it down by
+      // the empty planes: one funnel shift while m + lead stays below 32
+      const uint32_t down = m + lead;
+      if (any_lane_active(down > 31u)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) u[i] = alignbit(A[i], u[i], m) >> lead;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) u[i] = alignbit(A[i], u[i], down);
       }
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) u[i] >>= (lead & 31u);  // lead >= 32 only in blocks emptied above
     inverse_transform(u, E, out);
   }
 }
