@@ -73,27 +73,35 @@ def algorithmic_bytes(kernel, n, rate, k=2):
 SETTLE_MS = 60.0   # untimed launches before a kernel is timed on its own (see time_events)
 
 
-def time_events(fn, reps, torch, skip=0, settle_ms=SETTLE_MS):
-    """Per-call durations (ms) measured with HIP events on the launch stream; fn gets the
+def time_events(fn, reps, torch, skip=0, settle_ms=SETTLE_MS, batch_ms=0.6):
+    """Per-launch durations (ms) measured with HIP events on the launch stream; fn gets the
     iteration number.  Before timing, fn is launched untimed for `settle_ms` of wall time:
     back-to-back launches of one kernel go through a clock transient on this GPU (the same
     launch takes up to 40 % longer between about 3 and 15 ms after the load starts, then
-    settles), so a kernel timed on its own is timed in its settled state."""
+    settles), so a kernel timed on its own is timed in its settled state.  An event pair
+    costs several microseconds on the stream, so short launches are timed in batches of
+    back-to-back launches that last about `batch_ms` between one pair of events; each of
+    the `reps` figures returned is a batch's time divided by its launches."""
     i = 0
+    per_launch_ms = None
     t0 = time.perf_counter()
     while settle_ms > 0 and (time.perf_counter() - t0) * 1e3 < settle_ms:
+        t1 = time.perf_counter()
         for _ in range(10):
             fn(i)
             i += 1
         torch.cuda.synchronize()
+        per_launch_ms = (time.perf_counter() - t1) * 1e3 / 10
+    batch = 1 if not per_launch_ms else int(min(64, max(1, round(batch_ms / per_launch_ms))))
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for a, b in evs:
         a.record()
-        fn(i)
-        i += 1
+        for _ in range(batch):
+            fn(i)
+            i += 1
         b.record()
     torch.cuda.synchronize()
-    return [a.elapsed_time(b) for a, b in evs][skip:]
+    return [a.elapsed_time(b) / batch for a, b in evs][skip:]
 
 
 def frac(nbytes, ms):
@@ -181,11 +189,7 @@ def config_table(torch, zc, workloads, dev, reps=20):
                  "reduce_k2_uncompressed_GBps": round(4 * n / (mr * 1e-3) / 1e9, 1)}
             e.update(error_stats(torch, ys[0], xs[0]))
             if config == 1:
-                # a 4 MiB message is about 1 us of traffic: launch-bound; also as a batch of back-to-back launches
-                t0 = time_events(lambda i: [zc.zc_compress(xs[j], rate, d_out=cs[j]) for j in range(m)], 3, torch)
-                t1 = time_events(lambda i: [zc.zc_decompress(cs[j], n, rate, d_out=ys[j]) for j in range(m)], 3, torch)
-                e["compress_ms_in_batch"] = round(float(np.median(t0)) / m, 5)
-                e["decompress_ms_in_batch"] = round(float(np.median(t1)) / m, 5)
+                # a 4 MiB message is about 1 us of traffic: the figures are launch costs
                 e["note"] = "launch-bound: correctness workload"
             entries[label] = e
             del xs, cs, rs, ys, x0
