@@ -411,7 +411,6 @@ def main():
 def extras(torch, zc, workloads, dev, x, incoming, c, r, y, n, rate):
     """Figures outside `value`, on the headline buffer: the two fused ring-hop variants, the
     buffer as a bf16 message, 4 x 4 blocks on a matrix of the same size, the lossless codec."""
-    ev = lambda: torch.cuda.Event(enable_timing=True)
     hop_mixed = float(np.median(time_events(lambda i: zc.zc_reduce_mixed([incoming], x, n, rate, d_out=r), 12, torch)))
     hop_raw = float(np.median(time_events(lambda i: zc.zc_reduce_decompress([incoming], x, n, rate, d_out=y), 12, torch)))
     mixed_bytes = n * 4 + 2 * (n * rate // 8)
@@ -424,19 +423,9 @@ def extras(torch, zc, workloads, dev, x, incoming, c, r, y, n, rate):
     xh = x.to(torch.bfloat16)
     yh = torch.empty_like(xh)
     ch = torch.empty_like(c)
-    half_marks = []
-    for _ in range(12):
-        e = [ev() for _ in range(3)]
-        e[0].record()
-        zc.zc_compress_half(xh, rate, d_out=ch)
-        e[1].record()
-        zc.zc_decompress_half(ch, n, rate, d_out=yh)
-        e[2].record()
-        half_marks.append(e)
-    torch.cuda.synchronize()
+    hc = float(np.median(time_events(lambda i: zc.zc_compress_half(xh, rate, d_out=ch), 12, torch)))
+    hd = float(np.median(time_events(lambda i: zc.zc_decompress_half(ch, n, rate, d_out=yh), 12, torch)))
     hb = n * 2 + n * rate // 8
-    hc = float(np.median([m[0].elapsed_time(m[1]) for m in half_marks[2:]]))
-    hd = float(np.median([m[1].elapsed_time(m[2]) for m in half_marks[2:]]))
     half_precision = {"dtype": "bf16", "compress_ms": round(hc, 4), "decompress_ms": round(hd, 4),
                       "compress_hbm_frac": frac(hb, hc), "decompress_hbm_frac": frac(hb, hd)}
     del xh, yh, ch
@@ -448,18 +437,8 @@ def extras(torch, zc, workloads, dev, x, incoming, c, r, y, n, rate):
     blocks_4x4 = {"matrix": "%dx%d rank-8 + noise" % (m_rows, m_cols)}
     for r2 in (4, 8):
         cm = torch.empty(zc.zc2d_compressed_size(m_rows, m_cols, r2), dtype=torch.uint8, device=dev)
-        m2 = []
-        for _ in range(12):
-            e = [ev() for _ in range(3)]
-            e[0].record()
-            zc.zc2d_compress(xm, r2, d_out=cm)
-            e[1].record()
-            zc.zc2d_decompress(cm, m_rows, m_cols, r2, d_out=ym)
-            e[2].record()
-            m2.append(e)
-        torch.cuda.synchronize()
-        tc = float(np.median([m[0].elapsed_time(m[1]) for m in m2[2:]]))
-        td = float(np.median([m[1].elapsed_time(m[2]) for m in m2[2:]]))
+        tc = float(np.median(time_events(lambda i: zc.zc2d_compress(xm, r2, d_out=cm), 12, torch)))
+        td = float(np.median(time_events(lambda i: zc.zc2d_decompress(cm, m_rows, m_cols, r2, d_out=ym), 12, torch)))
         rm = torch.empty_like(cm)
         tr = float(np.median(time_events(lambda i: zc.zc2d_reduce_compressed([cm, cm], m_rows, m_cols, r2, d_out=rm), 12, torch)))
         del rm
@@ -483,18 +462,8 @@ def extras(torch, zc, workloads, dev, x, incoming, c, r, y, n, rate):
         yl = torch.empty_like(xl)
         comp(xl, d_out=cl)
         size = zc.zl_stream_bytes(cl)
-        ml = []
-        for _ in range(12):
-            e = [ev() for _ in range(3)]
-            e[0].record()
-            comp(xl, d_out=cl)
-            e[1].record()
-            decomp(cl[:size], n, d_out=yl)
-            e[2].record()
-            ml.append(e)
-        torch.cuda.synchronize()
-        tc = float(np.median([m[0].elapsed_time(m[1]) for m in ml[2:]]))
-        td = float(np.median([m[1].elapsed_time(m[2]) for m in ml[2:]]))
+        tc = float(np.median(time_events(lambda i: comp(xl, d_out=cl), 12, torch)))
+        td = float(np.median(time_events(lambda i: decomp(cl[:size], n, d_out=yl), 12, torch)))
         message = xl.element_size() * n
         moved = message + size
         as_int = torch.int16 if half else torch.int32

@@ -168,9 +168,19 @@ ZC_DEV void lift_forward(int32_t& a, int32_t& b, int32_t& c, int32_t& d) {
 // x: the block row-major as fp32 bit patterns.  Returns E and the negabinary words in
 // coefficient order.
 ZC_DEV void forward_transform(const uint32_t (&x)[16], uint32_t& E, uint32_t (&u)[16]) {
+  // largest magnitude as a bit pattern (on the device a float maximum with |x| operands, as in
+  // the 1-D codec: the same pattern for finite values, a third of the instructions)
+#if defined(__HIP_DEVICE_COMPILE__)
+  float mf = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; i += 2)
+    asm("v_max3_f32 %0, |%1|, |%2|, |%3|" : "=v"(mf) : "v"(mf), "v"(zc::bits_to_float(x[i])), "v"(zc::bits_to_float(x[i + 1])));
+  const uint32_t m = __builtin_bit_cast(uint32_t, mf);
+#else
   uint32_t m = 0;
 #pragma unroll
   for (int i = 0; i < 16; ++i) m = umax(m, x[i] & 0x7FFFFFFFu);
+#endif
   E = (m >> 23) + (m != 0u ? 1u : 0u);
   const int scale = 127 + kFractionBits - (int)E;
   int32_t q[16];
@@ -255,7 +265,7 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32
 ZC_DEV void inverse_transform(uint32_t (&u)[16], uint32_t E, float (&out)[16]) {
   int32_t q[16];
 #pragma unroll
-  for (int c = 0; c < 16; ++c) q[kOrder.v[c]] = zc::from_negabinary(u[c]);
+  for (int c = 0; c < 16; ++c) q[kOrder.v[c]] = zc::negabinary_to_int(u[c]);
 #pragma unroll
   for (int c = 0; c < 4; ++c) zc::inverse_lift(q[c], q[4 + c], q[8 + c], q[12 + c]);
 #pragma unroll
@@ -267,6 +277,15 @@ ZC_DEV void inverse_transform(uint32_t (&u)[16], uint32_t E, float (&out)[16]) {
 
 // One plane of the embedded code, read from the bottom of the window W.  Returns the
 // plane's bit of each coefficient.
+//
+// The group tests are read in steps that all lanes of the wavefront take together.  A step
+// looks the next bits up in the token table; if in every lane that still reads this plane
+// the entry's tokens lie inside the budget, the step is just the entry applied (lanes that
+// are done apply an empty entry).  Otherwise (some lane's first token is longer than the
+// look-ahead, or its budget ends inside the entry's bits) the step takes the general form:
+// per lane the entry if it fits, else one token by count-trailing-zeros with the limits
+// applied.  Budgets of the lanes of a wavefront end within a few steps of each other, so the
+// general form is needed near a block's end only.
 template <int NW, class AnyActive>
 ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t& n, uint32_t& left,
                              AnyActive any_lane_active) {
@@ -274,26 +293,34 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
   uint32_t pat = W[0] & ((1u << vlen) - 1u);
   zc::shift_out<NW>(W, vlen);
   left -= vlen;
-  // i: first coefficient not yet known to be significant; watch: the same while group
-  // tests remain, 16 once the closing zero has been read
-  uint32_t i = n, watch = n;
+  // i: first coefficient not yet known to be significant; closed: the plane's closing zero
+  // has been read or its last coefficient dealt with
+  uint32_t i = n, closed = n >> 4;
   for (;;) {
-    const bool active = watch < 16u && left > 0u;
+    const bool active = closed == 0u && left > 0u;
     if (!any_lane_active(active)) break;
-    if (active) {
-      // all the tokens that lie whole in the next bits, if the budget covers them
-      const uint32_t e = token[(umin(15u - i, (uint32_t)kLookahead) << kLookahead) + (W[0] & ((1u << kLookahead) - 1u))];
-      const uint32_t t_used = (e >> 16) & 15u, t_passed = (e >> 12) & 15u;
-      const bool fast = t_used != 0u && t_used <= left;
-      // otherwise one token with the limits applied (its group bit is a one, or the table
-      // would have served): zeros up to the one; the run ends at the last coefficient or
-      // at the budget
+    // all the tokens that lie whole in the next bits
+    const uint32_t e = token[(umin(15u - i, (uint32_t)kLookahead) << kLookahead) + (W[0] & ((1u << kLookahead) - 1u))];
+    const uint32_t t_used = (e >> 16) & 15u;
+    const bool fits = t_used != 0u && t_used <= left;
+    if (!any_lane_active(active && !fits)) {
+      const uint32_t a = active ? e : 0u;
+      pat |= (a & 0x3FFu) << i;
+      i += (a >> 12) & 15u;
+      closed |= a >> 20;
+      const uint32_t used = (a >> 16) & 15u;
+      zc::shift_out<NW>(W, used);
+      left -= used;
+    } else if (active) {
+      // one token with the limits applied where the entry does not fit (its group bit is a one,
+      // or the table would have served): zeros up to the one; the run ends at the last
+      // coefficient or at the budget
       const uint32_t room = umin(15u - i, left - 1u);
       const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
-      const uint32_t used = fast ? t_used : 1u + z + (z < room ? 1u : 0u);
-      pat |= (fast ? (e & 0x3FFu) : 1u << z) << i;
-      i += fast ? t_passed : z + 1u;
-      watch = (fast && (e >> 20) != 0u) ? 16u : i;
+      const uint32_t used = fits ? t_used : 1u + z + (z < room ? 1u : 0u);
+      pat |= (fits ? (e & 0x3FFu) : 1u << z) << i;
+      i += fits ? (e >> 12) & 15u : z + 1u;
+      closed |= (fits ? e >> 20 : 0u) | (i >> 4);
       zc::shift_out<NW>(W, used);
       left -= used;
     }

@@ -216,9 +216,8 @@ __global__ __launch_bounds__(kThreads) void decompress2d_kernel(const uint8_t* _
     Cursor next = cur;
     next.advance(w);
     const bool more = next.b < w.blocks;
-    if (!more) next = cur;
     uint32_t Wn[NW];
-    load_words<NW>(in + next.b * zc2d::Traits<RATE>::kBlockBytes, Wn);   // the next block's stream, ahead of time
+    if (more) load_words<NW>(in + next.b * zc2d::Traits<RATE>::kBlockBytes, Wn);   // the next block's stream, ahead of time
     float y[16];
     zc2d::decode_block<RATE>(W, token, y, AnyLane());
     store_block<DT>(out, w, cur, y);

@@ -21,10 +21,11 @@ def shim():
     newest = max(os.path.getmtime(f) for f in [SRC] + HDRS)
     if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
         subprocess.check_call(["g++", "-std=c++17", "-O2", "-fwrapv", "-ffp-contract=off", "-shared", "-fPIC",
-                               "-fconstexpr-ops-limit=200000000", SRC, "-o", LIB])
+                               "-fconstexpr-ops-limit=200000000", "-pthread", SRC, "-o", LIB])
     L = ctypes.CDLL(LIB)
     L.zc2d_host_encode_blocks.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.zc2d_host_decode_blocks.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.zc2d_host_wave.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int]
     return L
 
 
@@ -70,3 +71,28 @@ def test_encode_and_decode_match_reference(o2, shim, rate):
         assert shim.zc2d_host_decode_blocks(rate, s.ctypes.data, len(s), gotd.ctypes.data) == 0
         bad = np.flatnonzero((gotd.view(np.uint32) != wantd.view(np.uint32)).any(axis=1))
         assert bad.size == 0, (rate, trial, bad[:5])
+
+
+@pytest.mark.parametrize("rate", RATES)
+def test_lockstep_lanes_match_reference(o2, shim, rate):
+    """The per-lane codec with its wavefront-wide loop decisions taken by a vote among lanes that run
+    in lockstep (16 and 5 lanes), on blocks that need very different numbers of steps side by side
+    (shuffled), and on arbitrary bytes: what a lane decodes must not depend on its neighbours."""
+    rng = np.random.default_rng(700 + rate)
+    x = _blocks()
+    x = np.ascontiguousarray(x[rng.permutation(len(x))[:1200]])
+    want = np.stack([o2.encode_block(b, rate) for b in x])
+    wantd = np.stack([o2.decode_block(b, rate) for b in want])
+    junk = rng.integers(0, 256, size=(1200, 2 * rate), dtype=np.uint8)
+    junk[::3] &= rng.integers(0, 256, size=junk[::3].shape, dtype=np.uint8)
+    with np.errstate(all="ignore"):
+        wantj = np.stack([o2.decode_block(b, rate) for b in junk])
+    for lanes in (16, 5):
+        got = np.zeros_like(want)
+        assert shim.zc2d_host_wave(rate, 1, x.ctypes.data, len(x), got.ctypes.data, lanes) == 0
+        assert np.array_equal(got, want), (rate, lanes)
+        for stream, expect in ((want, wantd), (junk, wantj)):
+            gotd = np.zeros_like(expect)
+            assert shim.zc2d_host_wave(rate, 0, stream.ctypes.data, len(stream), gotd.ctypes.data, lanes) == 0
+            bad = np.flatnonzero((gotd.view(np.uint32) != expect.view(np.uint32)).any(axis=1))
+            assert bad.size == 0, (rate, lanes, bad[:5])
