@@ -185,32 +185,73 @@ constexpr Enc4Table build_enc4_table() {
   return t;
 }
 
-// Decoder, one plane per step.  Index = (n*8 + min(bits left, 7))*128 + next 7 stream
-// bits.  Entry = the plane's bit of coefficient i at bit 8*i | bits consumed << 1 |
-// (next state) << 12, which is the byte offset of that state's 8*128 entries.  With no
-// bits left nothing is read and nothing changes any more, and the entry names state 4 as
-// the next one: "state of at least 3" then also covers "budget spent", which is the one
-// test the decoder's plane loop makes.
+// Decoder tables for the planes read before three coefficients are significant (states
+// 0, 1, 2; a fourth "idle" row of empty entries serves lanes that are past that point or out
+// of budget, so that all lanes of a wavefront can step together).
+//
+// Entry (both tables): bits 1:0 of byte i = the bits of coefficient i in the planes read
+// (the earlier plane in the higher bit) | planes read << 2 | stream bits used << 4 |
+// (next state's row: 0, 1, 2 or 3 = idle) << 11.
+//
+// Look-ahead table: index = row*512 + next 9 stream bits, used when every lane that still
+// reads has at least 9 bits of budget left, so that the budget cannot cut what an entry reads.
+// An entry holds one plane, and a second one if that one also lies whole within the 9 bits
+// and the first left the state below 3.
+//
+// Budget table: index = row*256 + (2^a - 1) + (next a stream bits), a = min(bits left, 7):
+// one plane read with only a bits available, which resolves a code word cut by the budget (the
+// one goes to the lowest index still possible); a = 0 reads nothing and leads to the idle row.
 //
 // Behind these, 256 entries for two planes at once when at least three coefficients are
 // significant.  A plane is then four stream bits that are the plane's bits as they are
 // (in state 3 the fourth is the group test of the one coefficient left, which is that
-// coefficient's bit), whatever the state becomes.  Index = the next 8 stream bits, those
-// past the budget cleared; entry = for coefficient i, at bit 8*i, its bit of the first
-// plane << 1 | its bit of the second.
-constexpr int kDecPlaneEntries = 5 * 8 * 128;
+// coefficient's bit), whatever the state becomes.  Index = the next 8 stream bits; entry =
+// for coefficient i, at bit 8*i, its bit of the first plane << 1 | its bit of the second.
+constexpr int kDecLook = 9;
+constexpr int kDecLookEntries = 4 << kDecLook;
+constexpr int kDecBudgetEntries = 4 * 256;
+constexpr int kDecPlaneEntries = kDecLookEntries + kDecBudgetEntries;
+constexpr uint32_t kDecIdle = 3u << 11;   // state code of the idle row (the codes are the rows' byte offsets in the look-ahead table)
 struct DecTable { uint32_t v[kDecPlaneEntries + 256]; };
+
+constexpr uint32_t spread_planes(uint32_t first, uint32_t second, int planes) {
+  uint32_t e = 0;
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t b = planes == 2 ? (((first >> i) & 1u) << 1) | ((second >> i) & 1u) : (planes == 1 ? (first >> i) & 1u : 0u);
+    e |= b << (8 * i);
+  }
+  return e;
+}
 
 constexpr DecTable build_dec_table() {
   DecTable t{};
-  for (int n = 0; n <= 4; ++n)
-    for (int avail = 0; avail < 8; ++avail)
-      for (int s = 0; s < 128; ++s) {
-        PlaneBits r = read_one_plane(n, avail, (uint32_t)s);
-        if (avail == 0) r.next = 4;
-        uint32_t spread = (r.p & 1u) | (r.p & 2u) << 7 | (r.p & 4u) << 14 | (r.p & 8u) << 21;
-        t.v[(n * 8 + avail) * 128 + s] = spread | (uint32_t)r.used << 1 | (uint32_t)r.next << 12;
+  const uint32_t idle = 3u << 11;
+  for (int n = 0; n < 3; ++n)
+    for (int s = 0; s < (1 << kDecLook); ++s) {
+      const PlaneBits a = read_one_plane(n, 16, (uint32_t)s);   // a plane is at most 7 bits long: always inside the 9
+      uint32_t planes = 1, used = (uint32_t)a.used, bits = spread_planes(a.p, 0, 1);
+      int next = a.next;
+      if (a.next < 3) {
+        const PlaneBits b = read_one_plane(a.next, 16, (uint32_t)s >> a.used);
+        if (a.used + b.used <= kDecLook) {
+          planes = 2;
+          used += (uint32_t)b.used;
+          bits = spread_planes(a.p, b.p, 2);
+          next = b.next;
+        }
       }
+      t.v[(n << kDecLook) + s] = bits | planes << 2 | used << 4 | (next < 3 ? (uint32_t)next << 11 : idle);
+    }
+  for (int s = 0; s < (1 << kDecLook); ++s) t.v[(3 << kDecLook) + s] = idle;
+  for (int n = 0; n < 3; ++n)
+    for (int a = 0; a <= 7; ++a)
+      for (int s = 0; s < (1 << a); ++s) {
+        const PlaneBits r = read_one_plane(n, a, (uint32_t)s);
+        const uint32_t e = a == 0 ? idle
+                                  : spread_planes(r.p, 0, 1) | 1u << 2 | (uint32_t)r.used << 4 | (r.next < 3 ? (uint32_t)r.next << 11 : idle);
+        t.v[kDecLookEntries + n * 256 + ((1 << a) - 1) + s] = e;
+      }
+  for (int s = 0; s < 256; ++s) t.v[kDecLookEntries + 3 * 256 + s] = idle;
   for (uint32_t b = 0; b < 256; ++b) {
     uint32_t e = 0;
     for (int i = 0; i < 4; ++i) e |= ((((b >> i) & 1u) << 1) | ((b >> (4 + i)) & 1u)) << (8 * i);
@@ -527,14 +568,15 @@ ZC_DEV void inverse_transform(const uint32_t (&u)[4], uint32_t E, float (&out)[4
 
 // W holds the block (bits beyond 4*RATE zero).
 //
-// Rates above 4 decode in two phases.  (1) Planes are read one per step through the table
-// while any lane of the wavefront is still in a state below 3 with bits left; all lanes step
-// together, so the number m of planes read is the same in every lane.  (2) From state 3 on
-// a plane is four stream bits that are the plane's bits as they are (in state 3 the fourth
+// Rates above 4 decode in two phases.  (1) While any lane of the wavefront is in a state
+// below 3 with bits left, all lanes step together through the tables: one or two planes per
+// step from the look-ahead table, or, when some reading lane is within 9 bits of its budget,
+// one plane from the budget table; lanes past that point take empty entries.  (2) From state 3
+// on a plane is four stream bits that are the plane's bits as they are (in state 3 the fourth
 // is the group test of the one coefficient left, which is that coefficient's bit), and bits
 // past the budget are zeros in the window and decode as the zeros that unseen bits are; so
 // the rest of the window is taken as it stands, eight planes per 32 bits through the pair
-// table, with no loop, no budget and no state, and joined to the m planes of phase 1.
+// table, with no loop, no budget and no state, and joined to the planes of phase 1.
 template <int RATE, class AnyActive>
 ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab, float (&out)[4],
                          AnyActive any_lane_active) {
@@ -549,8 +591,6 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
 #pragma unroll
     for (int i = 0; i < 4; ++i) out[i] = __builtin_ldexpf(q[i], ex);
   } else {
-    constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
-    constexpr int kGroups = (kMaxPlanes + 7) / 8;
     // literal words of phase 2: at least one bit is gone after phase 1, and at most 31 planes remain
     constexpr int kLiteral = (kPayload - 1 + 31) / 32 < 4 ? (kPayload - 1 + 31) / 32 : 4;
     // leading empty planes = zero bits at the start of the payload
@@ -568,48 +608,67 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     }
     lead = umin(lead, (uint32_t)kPayload);
     uint32_t left = (uint32_t)kPayload - lead;
-    // keep the next stream bit at bit 2 of the window: bits 8..2 index the table directly
+    // keep the next stream bit at bit 2 of the window: bits 10..2 index the look-ahead table directly
     shift_right<NW>(W, lead + 6u);
+    uint32_t state = 0;
     // a zero block ignores its payload; after 32 empty planes nothing is left to decode
     if (E == 0u || (kPayload > 32 && lead >= 32u)) {
       left = 0u;
       lead = 0u;
+      state = kDecIdle;
 #pragma unroll
       for (int j = 0; j < NW; ++j) W[j] = 0u;
     }
-    // phase 1.  A[i] collects the planes of coefficient i, the latest in bit 0.
-    uint32_t state = 0, A[4] = {0u, 0u, 0u, 0u};
-    uint32_t m = 0;
-    bool open = true;
-#pragma unroll
-    for (int g = 0; g < kGroups; ++g) {
-      if (open) {
-        uint32_t acc = 0, mg = 0;   // byte i of acc = this group's planes of coefficient i
+    // phase 1.  A[i] collects the planes of coefficient i, the latest in bit 0; m counts them
+    // (per lane: a step reads one or two planes, or none in a lane that is idle).
+    uint32_t A[4] = {0u, 0u, 0u, 0u}, m = 0;
+    // one group of up to four steps: byte i of acc = the group's planes of coefficient i (at most eight)
+    auto group = [&](uint32_t& acc, uint32_t& mg) {
+      uint32_t s = 0;
 #pragma unroll 1
-        for (; mg < 8u; ++mg) {
-          if (!any_lane_active(state < 0x3000u)) break;
-          const uint32_t e = tab.dec[(umin(left, 7u) << 9 | ((W[0] & 0x1FCu) | state)) >> 2];
-          const uint32_t len = (e >> 1) & 7u;
-          acc = (acc << 1) | (e & 0x01010101u);
-          shift_out<NW>(W, len);
-          left -= len;
-          state = e & 0x7000u;
+      for (; s < 4u; ++s) {
+        const bool reading = state < kDecIdle;
+        if (!any_lane_active(reading)) break;
+        uint32_t e;
+        if (any_lane_active(reading && left < (uint32_t)kDecLook)) {
+          const uint32_t mask = (1u << umin(left, 7u)) - 1u;
+          e = tab.dec[kDecLookEntries + (state >> 3) + mask + ((W[0] >> 2) & mask)];
+        } else {
+          e = tab.dec[(state | (W[0] & (((1u << kDecLook) - 1u) << 2))) >> 2];
         }
+        const uint32_t planes = (e >> 2) & 3u, used = (e >> 4) & 15u;
+        acc = (acc << planes) | (e & 0x03030303u);
+        mg += planes;
+        shift_out<NW>(W, used);
+        left -= used;
+        state = e & kDecIdle;
+      }
+      return s == 4u;
+    };
+    {
+      uint32_t acc = 0;
+      bool open = group(acc, m);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) A[i] = (acc >> (8 * i)) & 0xFFu;
+      // more groups only for blocks that stay below three significant coefficients for long; no
+      // more than 32 planes are kept (a block has no more, whatever the stream goes on to say)
+#pragma unroll 1
+      for (int g = 1; g < 8 && open; ++g) {
+        uint32_t mg = 0;
+        acc = 0;
+        open = group(acc, mg);
+        const uint32_t take = umin(mg, 32u - m);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const uint32_t planes = (acc >> (8 * i)) & 0xFFu;
-          A[i] = g == 0 ? planes : (A[i] << mg) | planes;
+          const uint32_t planes = ((acc >> (8 * i)) & 0xFFu) >> (mg - take);
+          A[i] = take >= 32u ? planes : (A[i] << take) | planes;
         }
-        m += mg;
-        open = mg == 8u;
+        m += take;
       }
     }
+    // phase 2.  G[j]: byte i = the next eight literal planes of coefficient i, the first in bit 7
     uint32_t u[4];
-    if (m >= 32u) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) u[i] = A[i] >> lead;   // lead is below 32 (blocks with more were emptied above)
-    } else {
-      // phase 2.  G[j]: byte i = planes m + 8j .. m + 8j + 7 of coefficient i, the first in bit 7
+    {
       const uint32_t* pair = tab.dec + kDecPlaneEntries;
       uint32_t G[kLiteral];
 #pragma unroll
@@ -620,7 +679,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        // B = the literal planes of coefficient i from bit 31 down
+        // the literal planes of coefficient i from bit 31 down
         uint32_t B;
         if constexpr (kLiteral == 1) {
           B = permute_bytes(0u, G[0], 0x000c0c0cu | (uint32_t)i << 24);
@@ -631,12 +690,12 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
         }
         u[i] = B;
       }
-      // the m planes of phase 1 (m is 1..31 here) above the literal ones, and all of it down by
-      // the empty planes: one funnel shift while m + lead stays below 32
+      // the m planes of phase 1 above the literal ones, and all of it down by the empty planes:
+      // one funnel shift while m + lead stays below 32
       const uint32_t down = m + lead;
       if (any_lane_active(down > 31u)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) u[i] = alignbit(A[i], u[i], m) >> lead;
+        for (int i = 0; i < 4; ++i) u[i] = (m >= 32u ? A[i] : alignbit(A[i], u[i], m)) >> lead;
       } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) u[i] = alignbit(A[i], u[i], down);
