@@ -229,15 +229,34 @@ def config_table(torch, zc, workloads, dev, reps=20):
                         "reduce_k8_plus_decompress_ms": round(tk8, 4), "k8_hbm_frac": frac(k8_bytes, tk8)}
         if nsets == 1:
             share[label]["note"] = "16 MiB per chunk: served from the last-level cache, not HBM"
+            direct(0)
+            torch.cuda.synchronize()
+            direct_sum = finals[0].clone()
+            chain(0)
+            torch.cuda.synchronize()
             chained = finals[0].clone()
+            # the same eight launches as one HIP graph (the chain is launch-bound: 18 us kernels)
+            side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+            comp, acc, final = sets[0], accs[0], finals[0]
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                zc.zc_reduce_compressed([comp[0], comp[1]], n, rate, d_out=acc, stream=side)
+                for j in range(2, 8):
+                    zc.zc_reduce_compressed([acc, comp[j]], n, rate, d_out=acc, stream=side)
+                zc.zc_decompress(acc, n, rate, d_out=final, stream=side)
+            final.zero_()
+            tg = float(np.median(time_events(lambda i: graph.replay(), reps, torch)))
+            share[label]["chain_as_hip_graph_ms"] = round(tg, 4)
+            share[label]["graph_equals_eager"] = bool(torch.equal(final.view(torch.int32), chained.view(torch.int32)))
+            del graph
         del sets, accs, finals
     total = torch.zeros(n, dtype=torch.float64, device=dev)
     for _, b in bufs:
         total += torch.from_numpy(b).to(dev).double()
-    err = chained.double() - total
-    share["ring_chain_error_vs_exact_sum"] = {"max_abs": float("%.4g" % float(err.abs().max())),
-                                              "rmse": float("%.4g" % float(err.pow(2).mean().sqrt())),
-                                              "sum_std": float("%.4g" % float(total.std()))}
+    for key, got in (("ring_chain_error_vs_exact_sum", chained), ("reduce_k8_error_vs_exact_sum", direct_sum)):
+        err = got.double() - total
+        share[key] = {"max_abs": float("%.4g" % float(err.abs().max())), "rmse": float("%.4g" % float(err.pow(2).mean().sqrt())),
+                      "sum_std": float("%.4g" % float(total.std()))}
     out["5"] = share
     return out
 
