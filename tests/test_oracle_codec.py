@@ -274,3 +274,31 @@ def test_ring_hop_variants_are_compositions(oracle):
     with pytest.raises(ValueError):
         oracle.reduce_mixed([], local, n, 8)
 
+
+
+def test_requantising_chain_error_per_rate(oracle):
+    """A ring that re-encodes the running sum at every hop: with eight payload bits per block
+    (rate 4) the error of the running sum about doubles per hop, at rate 8 it grows about
+    linearly and stays a fraction of the sum, at rate 16 it is negligible; one 8-way reduce
+    of the same chunks re-encodes once and stays close to one compression's error."""
+    bufs = [b for _, b in workloads.config_buffers(5, 10)]
+    n = bufs[0].size
+    total = np.sum([b.astype(np.float64) for b in bufs], axis=0)
+    rmse = {}
+    for rate in (4, 8, 16):
+        comp = [oracle.compress(b, rate) for b in bufs]
+        acc, partial, per_hop = comp[0], bufs[0].astype(np.float64), []
+        for j in range(1, 8):
+            acc = oracle.reduce_compressed([acc, comp[j]], n, rate)
+            partial = partial + bufs[j]
+            per_hop.append(np.sqrt(np.mean((oracle.decompress(acc, n, rate) - partial) ** 2)))
+        direct = oracle.decompress(oracle.reduce_compressed(comp, n, rate), n, rate)
+        rmse[rate] = (per_hop, np.sqrt(np.mean((direct - total) ** 2)))
+    std = total.std()
+    hops4, direct4 = rmse[4]
+    assert all(1.7 < b / a < 2.3 for a, b in zip(hops4[:-1], hops4[1:])) and hops4[-1] > 20 * std
+    assert direct4 < 2.5 * std
+    hops8, direct8 = rmse[8]
+    assert hops8[-1] < 6 * hops8[0] and hops8[-1] < 0.3 * std and direct8 < 0.15 * std
+    assert all(b > a for a, b in zip(hops8[:-1], hops8[1:]))
+    assert rmse[16][0][-1] < 1e-3 * std
