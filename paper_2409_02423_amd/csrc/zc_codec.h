@@ -12,19 +12,24 @@
 //
 // How the bit-plane code is computed here (instead of bit by bit):
 //   * The state of the plane coder is only n in {0..4}, the number of leading
-//     coefficients already significant.  The encoder looks up two planes at a time:
-//     (n, top two bits of each of the four coefficient words) -> code word of at most
-//     14 bits, its length and the next state.  The decoder looks up one plane at a
-//     time: (n, bits left in the budget capped at 7, next 7 stream bits) -> the
-//     plane's four bits, bits consumed, next state; this table also resolves a code
-//     word cut short by the budget.  At rate 4 the payload is a single byte and one
+//     coefficients already significant, and from n = 3 on a plane is coded as its four
+//     bits as they are.  So both coders walk their tables only until every lane of the
+//     wavefront has three significant coefficients (or no budget left) and handle the
+//     rest of the block as a literal string of planes, without a loop (see encode_block
+//     and decode_block).
+//   * Encoder table: (n, two planes as a byte of the literal string) -> code word of at
+//     most 14 bits, its length and the next state.  Decoder tables: (n, next 9 stream
+//     bits) -> one or two planes, bits used, next state, while the budget cannot cut
+//     what is read; (n, bits left capped at 7, that many stream bits) -> one plane near
+//     the budget's end, which also resolves a code word cut short by the budget.  At
+//     rate 4 the payload is a single byte: one 8192-entry table encodes it and one
 //     256-entry table holds the decoded block up to its power-of-two scale.
-//   * Coefficient words are consumed from the top by funnel shifts, and decoded plane
-//     bits are collected four byte lanes at a time, so no bit transposition is needed.
+//   * Decoded plane bits are collected in four byte lanes, one per coefficient, so no bit
+//     transposition is needed; literal planes go through 256-entry spread / pair tables.
 //   * Empty leading planes cost one zero bit each and are skipped by a count of
 //     leading zeros (encoder) or trailing zeros of the payload (decoder).
 //   * The stream is built by shifting code words in at the top of a register window
-//     (one v_alignbit per word) and aligned once at the end.
+//     (one v_alignbit per word) and put in place by one funnel shift at the end.
 #ifndef ZC_CODEC_H
 #define ZC_CODEC_H
 

@@ -570,9 +570,9 @@ int compute_units() {
 
 // Workgroups per CU in the grid (each loops over tiles with a grid stride).  Eight
 // 256-thread workgroups fill a CU; launching several times that lets the dispatcher
-// even out the data-dependent coding time, which pays for every coder-bound kernel
-// (measured: 32 to 48 per CU is best at rates 8 and up and for the fused reduce; the
-// wide rate-4 kernels, whose wavefronts take 512 blocks per pass, like 64 and 24).
+// even out the data-dependent coding time (measured: between 8 and 64 per CU the compress
+// and decompress kernels differ by a few per cent, 32 to 48 is best for the fused reduce;
+// the wide rate-4 kernels, whose wavefronts take 512 blocks per pass, like 64 and 24).
 // The library reads no environment variable; only a build with -DZC_TUNING_KNOBS (never
 // the shipped one) lets ZC_WORKGROUPS_PER_CU override these numbers for tuning runs.
 enum Kernel { kCompress, kDecompress, kReduce };
