@@ -382,12 +382,18 @@ __global__ __launch_bounds__(kThreads) void decompress4_wide_kernel(const uint8_
   const zc::Tables tab = stage_decoder_table<4>(dec, nullptr);
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const size_t stride = (size_t)gridDim.x * (kThreads / 64);
-  size_t t = (size_t)blockIdx.x * (kThreads / 64) + wave;
+  // a workgroup's four wave tiles are neighbours (32 KiB of fp32 output); these groups of four
+  // are taken in region order, 1 MiB of output per region
+  constexpr int kRegionLg = 5;
+  const size_t groups = wave_tiles / (kThreads / 64), bulk = zc::region_bulk(groups, kRegionLg);
+  auto wave_tile = [&](size_t g) { return g < groups ? zc::region_order(g, bulk, kRegionLg) * (kThreads / 64) + wave : g * (kThreads / 64) + wave; };
+  size_t g = blockIdx.x;
+  size_t t = wave_tile(g);
   if (t >= wave_tiles) return;
   u32x4 v = *reinterpret_cast<const u32x4*>(in + t * 1024 + 16 * lane);
   for (;;) {
-    const size_t tn = t + stride;
+    const size_t gn = g + gridDim.x;
+    const size_t tn = wave_tile(gn);
     const bool more = tn < wave_tiles;
     u32x4 vn = v;
     if (more) vn = *reinterpret_cast<const u32x4*>(in + tn * 1024 + 16 * lane);
@@ -405,6 +411,7 @@ __global__ __launch_bounds__(kThreads) void decompress4_wide_kernel(const uint8_
     if (!more) break;
     v = vn;
     t = tn;
+    g = gn;
   }
 }
 

@@ -134,3 +134,9 @@ extern "C" int zc_host_decode_wave(int rate, const uint8_t* in, size_t blocks, f
   }
   return 0;
 }
+
+// The decompress kernels' tile order (see region_order in zc_codec.h), for a check that it is a
+// permutation of the tiles.
+extern "C" size_t zc_host_region_order(size_t v, size_t tiles, int lg) {
+  return zc::region_order(v, zc::region_bulk(tiles, lg), lg);
+}

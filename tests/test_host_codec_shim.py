@@ -29,6 +29,8 @@ def shim():
     L.zc_host_decode_blocks.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.zc_host_encode_wave.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int]
     L.zc_host_decode_wave.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int]
+    L.zc_host_region_order.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int]
+    L.zc_host_region_order.restype = ctypes.c_size_t
     return L
 
 
@@ -118,3 +120,18 @@ def test_lockstep_lanes_match_reference(oracle, shim, rate):
             assert shim.zc_host_decode_wave(rate, stream.ctypes.data, nb, got.ctypes.data, lanes) == 0
             bad = np.flatnonzero((got.view(np.uint32) != want.view(np.uint32)).reshape(-1, 4).any(axis=1))
             assert bad.size == 0, (rate, lanes, bad[:5])
+
+
+def test_region_order_is_a_permutation_of_the_tiles(shim):
+    """The tile order of the decompress kernels: every tile exactly once, whatever the tile count and
+    region size; whole groups of eight regions are reordered (indices with the same value mod 8 walk
+    through regions x, x + 8, ...), the rest stays in place."""
+    for lg in (0, 2, 5, 6, 8):
+        for tiles in (0, 1, 7, 8 << lg, (8 << lg) - 1, (8 << lg) + 1, 3 * (8 << lg) + 5, 12288, 65536, 36621):
+            got = [shim.zc_host_region_order(v, tiles, lg) for v in range(tiles)]
+            assert sorted(got) == list(range(tiles)), (lg, tiles)
+            bulk = (tiles >> (lg + 3)) << (lg + 3)
+            assert got[bulk:] == list(range(bulk, tiles))
+            if bulk:
+                mine = [got[v] for v in range(3, bulk, 8)]          # what XCD 3 walks through
+                assert mine == sorted(mine) and all((t >> lg) % 8 == 3 for t in mine)
