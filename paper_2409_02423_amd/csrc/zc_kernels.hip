@@ -212,10 +212,12 @@ __device__ __forceinline__ void store_stream(uint8_t* out, size_t j, const uint3
 
 // Blocks per lane and tile, from measurements on MI355X: the rate-4 compress and
 // decompress kernels have so little work per block that one block per lane is fastest;
-// everything else gains from four accesses in flight per lane.
+// the others gain from four accesses in flight per lane, except the fused reduce above
+// rate 4, which is bound by its arithmetic and runs 2 to 6 % faster with two (fewer
+// registers, more wavefronts per SIMD).
 template <int RATE> constexpr int compress_unroll() { return RATE == 4 ? 1 : 4; }
 template <int RATE> constexpr int decompress_unroll() { return RATE == 4 ? 1 : 4; }
-template <int RATE> constexpr int reduce_unroll() { return 4; }
+template <int RATE> constexpr int reduce_unroll() { return RATE == 4 ? 4 : 2; }
 
 template <int RATE, int U, int DT>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restrict__ in, size_t n,
