@@ -75,6 +75,17 @@ ZC_DEV uint32_t permute_bytes(uint32_t hi, uint32_t lo, uint32_t sel) {
 }
 
 ZC_DEV uint32_t count_leading_zeros(uint32_t x) { return x ? (uint32_t)__builtin_clz(x) : 32u; }
+// The same for x != 0; for x = 0 a value that callers may only use as a shift count for
+// zero words (the instruction gives -1 there, and the test for zero is saved).
+ZC_DEV uint32_t count_leading_zeros_nonzero(uint32_t x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  uint32_t r;
+  asm("v_ffbh_u32 %0, %1" : "=v"(r) : "v"(x));
+  return r;
+#else
+  return x ? (uint32_t)__builtin_clz(x) : 0xFFFFFFFFu;
+#endif
+}
 ZC_DEV uint32_t count_trailing_zeros(uint32_t x) { return x ? (uint32_t)__builtin_ctz(x) : 32u; }
 ZC_DEV uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 ZC_DEV uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
@@ -435,7 +446,10 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
   uint32_t E, u[4];
   forward_transform(x, E, u);
   // leading empty planes: one zero bit each
-  const uint32_t lead = count_leading_zeros(u[0] | u[1] | u[2] | u[3]);
+  // (at rate 4 the count only serves as a shift of the words and of the table's entry, which are
+  // zero when all words are)
+  const uint32_t lead = RATE == 4 ? count_leading_zeros_nonzero(u[0] | u[1] | u[2] | u[3])
+                                  : count_leading_zeros(u[0] | u[1] | u[2] | u[3]);
   const int32_t avail = kPayload - (int32_t)lead;
   uint32_t left = avail > 0 ? (uint32_t)avail : 0u;
 #pragma unroll
@@ -711,21 +725,20 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
   }
 }
 
-// Rate 4: sum += the decoded block, with one rounding per value as a decode followed by an
-// add would give.  Fused form: the table's entries are integers below 2^9 and 2^(E - 133) is
-// a representable (possibly subnormal) power of two, so their product is exact and the fused
-// multiply-add rounds the same sum once.  That holds while the product is finite; from
-// E = 252 on it may overflow (only arbitrary bytes or values of 2^127 and more produce such
-// an exponent), where a decoded infinity plus the sum is not what the fused form gives: the
-// caller then asks for the two-step form (see may_overflow4).
-template <bool TWO_STEPS>
-ZC_DEV void accumulate_block4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
-  const uint32_t E = W0 & 0xFFu;
-  const float* q = tab.dec4 + 4u * (E ? W0 >> 8 : 0u);
-  const int ex = (int)E - 127 - kFractionBits + 22;
-  if constexpr (TWO_STEPS) {
+// Rate 4 in the fused reduce: sum = (FIRST) or sum += (otherwise) the decoded block, with one
+// rounding per value as a decode followed by an add would give.
+//
+// Plain form, for exponent bytes 1..249 and for zero blocks whose payload is zero: the table's
+// entries are integers below 2^9 and 2^(E - 133) is a representable (possibly subnormal) power
+// of two, so their product is exact and the fused multiply-add rounds the same sum once; entry 0
+// is four zeros, so a zero block with a zero payload needs no test of its exponent byte.
+template <bool FIRST>
+ZC_DEV void accumulate_plain4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
+  const float* q = reinterpret_cast<const float*>(reinterpret_cast<const char*>(tab.dec4) + (((W0 >> 8) & 0xFFu) << 4));
+  const int ex = (int)(W0 & 0xFFu) - 127 - kFractionBits + 22;
+  if constexpr (FIRST) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sum[i] = sum[i] + __builtin_ldexpf(q[i], ex);
+    for (int i = 0; i < 4; ++i) sum[i] = __builtin_ldexpf(q[i], ex);
   } else {
     const float scale = __builtin_ldexpf(1.0f, ex);
 #pragma unroll
@@ -733,8 +746,23 @@ ZC_DEV void accumulate_block4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
   }
 }
 
-// Whether a rate-4 block's exponent byte is high enough for a decoded value to overflow.
-ZC_DEV bool may_overflow4(uint32_t W0) { return (W0 & 0xFFu) >= 250u; }
+// Careful form, for any block: a zero exponent byte ignores the payload, and the decoded value
+// is rounded (possibly to infinity: from E = 252 on the product overflows) before it is added.
+// Only arbitrary bytes or values of 2^127 and more produce blocks that need it.
+template <bool FIRST>
+ZC_DEV void accumulate_careful4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
+  const uint32_t E = W0 & 0xFFu;
+  const float* q = tab.dec4 + 4u * (E ? (W0 >> 8) & 0xFFu : 0u);
+  const int ex = (int)E - 127 - kFractionBits + 22;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) sum[i] = FIRST ? __builtin_ldexpf(q[i], ex) : sum[i] + __builtin_ldexpf(q[i], ex);
+}
+
+// Whether a block (W0 = its two bytes, zero-extended) is outside what the plain form covers:
+// exponent byte 250 and more, or exponent byte 0 over a nonzero payload.  W0 - 1 has 255 in
+// its low byte in the second case and E - 1 otherwise; the all-zero block wraps to a word with
+// the top bit set, which the signed compare leaves out.
+ZC_DEV bool unusual4(uint32_t W0) { return (int32_t)((W0 - 1u) & 0x800000FFu) >= 249; }
 
 // ---- tile order of the wide rate-4 decompress kernel ---------------------------------
 // That kernel is bound by its non-temporal stores of the fp32 output, and how the

@@ -474,6 +474,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
         for (int u = 0; u < U; ++u) load_values<kF32>(local, t * kTile + u * kThreads + threadIdx.x, loc[u]);
       }
       float s[U][4];
+      bool unusual = false;
 #pragma unroll
       for (int c = 0; c < k; ++c) {
         const bool last = c + 1 == k;
@@ -484,18 +485,14 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 #pragma unroll
           for (int u = 0; u < U; ++u) load_stream<RATE>(src, next + u * kThreads, Wn[u]);
         }
-        if (RATE == 4 && c > 0) {
-          // rate 4, chunks after the first: fused multiply-add, unless some block of this tile in
-          // some lane of the wavefront has an exponent byte at which a decoded value overflows
-          bool high = false;
+        if constexpr (RATE == 4) {
+          // rate 4: the plain form for every block, and a note of whether any block was outside
+          // what that form covers (the tile is then summed again, see below)
 #pragma unroll
-          for (int u = 0; u < U; ++u) high = high || zc::may_overflow4(W[u][0]);
-          if (AnyLane()(high)) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) zc::accumulate_block4<true>(W[u][0], tab, s[u]);
-          } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) zc::accumulate_block4<false>(W[u][0], tab, s[u]);
+          for (int u = 0; u < U; ++u) {
+            unusual = unusual || zc::unusual4(W[u][0]);
+            if (c == 0) zc::accumulate_plain4<true>(W[u][0], tab, s[u]);
+            else zc::accumulate_plain4<false>(W[u][0], tab, s[u]);
           }
         } else {
 #pragma unroll
@@ -511,6 +508,23 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
           for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < NW; ++i) W[u][i] = Wn[u][i];
+        }
+      }
+      if constexpr (RATE == 4) {
+        // some block of this tile, in some lane of the wavefront, has a nonzero payload under a
+        // zero exponent byte or an exponent byte at which a decoded value may overflow (arbitrary
+        // bytes, or values of 2^127 and more): fetch the tile's blocks again (nothing of the tile
+        // has been written yet) and sum them in the careful form
+        if (AnyLane()(unusual)) {
+          for (int c = 0; c < k; ++c) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              uint32_t Wc[NW];
+              load_stream<RATE>(chunks.p[c], t * kTile + u * kThreads + threadIdx.x, Wc);
+              if (c == 0) zc::accumulate_careful4<true>(Wc[0], tab, s[u]);
+              else zc::accumulate_careful4<false>(Wc[0], tab, s[u]);
+            }
+          }
         }
       }
 #pragma unroll

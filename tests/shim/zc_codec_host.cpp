@@ -140,3 +140,25 @@ extern "C" int zc_host_decode_wave(int rate, const uint8_t* in, size_t blocks, f
 extern "C" size_t zc_host_region_order(size_t v, size_t tiles, int lg) {
   return zc::region_order(v, zc::region_bulk(tiles, lg), lg);
 }
+
+// Rate 4 in the fused reduce: for each of the 65536 two-byte blocks W0, sum[W0] = (first) or
+// sum[W0] += (otherwise) the decoded block, in the form the reduce kernel picks for it (plain
+// unless unusual4 says otherwise; `form` 1 forces the plain form, 2 the careful one).
+// unusual[W0] receives unusual4's answer.
+extern "C" void zc_host_accumulate4_all(int first, int form, float* sum, uint8_t* unusual) {
+  for (uint32_t W0 = 0; W0 < 65536u; ++W0) {
+    float s[4];
+    std::memcpy(s, sum + 4 * W0, 16);
+    const bool odd = zc::unusual4(W0);
+    unusual[W0] = odd;
+    const bool careful = form == 2 || (form == 0 && odd);
+    if (careful) {
+      if (first) zc::accumulate_careful4<true>(W0, kTables, s);
+      else zc::accumulate_careful4<false>(W0, kTables, s);
+    } else {
+      if (first) zc::accumulate_plain4<true>(W0, kTables, s);
+      else zc::accumulate_plain4<false>(W0, kTables, s);
+    }
+    std::memcpy(sum + 4 * W0, s, 16);
+  }
+}

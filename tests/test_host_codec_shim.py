@@ -31,6 +31,8 @@ def shim():
     L.zc_host_decode_wave.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int]
     L.zc_host_region_order.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int]
     L.zc_host_region_order.restype = ctypes.c_size_t
+    L.zc_host_accumulate4_all.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    L.zc_host_accumulate4_all.restype = None
     return L
 
 
@@ -135,3 +137,38 @@ def test_region_order_is_a_permutation_of_the_tiles(shim):
             if bulk:
                 mine = [got[v] for v in range(3, bulk, 8)]          # what XCD 3 walks through
                 assert mine == sorted(mine) and all((t >> lg) % 8 == 3 for t in mine)
+
+
+def test_rate4_accumulate_forms_on_every_block(oracle, shim):
+    """The fused reduce at rate 4 adds a block to the running sum through a table and a fused
+    multiply-add (plain form) unless unusual4 flags the block, in which case the tile is summed
+    again in the careful form.  All 65536 two-byte blocks, against decode-then-add with the
+    reference decoder, for running sums of either sign, tiny, huge and infinite; the flagged blocks
+    are exactly those with exponent byte 250 and more or exponent byte 0 over a nonzero payload, and
+    the plain form is wrong on some of them (so the flag is needed)."""
+    W0 = np.arange(65536, dtype=np.uint16)
+    stream = W0.view(np.uint8)
+    decoded = oracle.decompress(stream, 4 * 65536, 4).reshape(-1, 4)
+    E, payload = W0 & 0xFF, W0 >> 8
+    expect_flag = (E >= 250) | ((E == 0) & (payload != 0))
+    flags = np.zeros(65536, dtype=np.uint8)
+    got = np.zeros((65536, 4), dtype=np.float32)
+    shim.zc_host_accumulate4_all(1, 0, got.ctypes.data, flags.ctypes.data)
+    assert np.array_equal(flags.astype(bool), expect_flag)
+    assert np.array_equal(got.view(np.uint32), decoded.view(np.uint32))
+    rng = np.random.default_rng(5)
+    plain_differs = 0
+    with np.errstate(over="ignore", invalid="ignore"):
+        for base in (0.0, -0.0, 1e-3, -1e-3, 1e-42, -3e38, 3e38, np.inf, -np.inf):
+            start = (np.float32(base) * (1 + rng.random((65536, 4), dtype=np.float32))).astype(np.float32)
+            want = (start + decoded).astype(np.float32)
+            for form in (0, 1):
+                got = start.copy()
+                shim.zc_host_accumulate4_all(0, form, got.ctypes.data, flags.ctypes.data)
+                same = (got.view(np.uint32) == want.view(np.uint32)) | (np.isnan(got) & np.isnan(want))
+                if form == 0:
+                    assert same.all(), (base, np.flatnonzero(~same.all(axis=1))[:5])
+                else:
+                    assert same[~expect_flag].all()
+                    plain_differs += int((~same[expect_flag]).any())
+    assert plain_differs > 0
