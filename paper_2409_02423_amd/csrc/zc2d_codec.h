@@ -70,9 +70,17 @@ constexpr Order kOrder = build_order();
 // Row r of a 16 x 16 bit matrix sits in half r >> 3 of word r & 7 (half 0 = bits 0..15).
 // The transpose leaves the matrix in the same arrangement, so it is its own inverse.
 ZC_DEV constexpr void transpose_halves(uint32_t (&a)[8]) {
-  // swap the 8 x 8 quadrants: bits 8..15 of row r with bits 0..7 of row r + 8
+  // swap the 8 x 8 quadrants: bits 8..15 of row r with bits 0..7 of row r + 8 (the two middle
+  // bytes of each word change places)
 #pragma unroll
-  for (int w = 0; w < 8; ++w) a[w] = (a[w] & 0xFF0000FFu) | ((a[w] & 0x0000FF00u) << 8) | ((a[w] >> 8) & 0x0000FF00u);
+  for (int w = 0; w < 8; ++w) {
+    if (__builtin_is_constant_evaluated())
+      a[w] = (a[w] & 0xFF0000FFu) | ((a[w] & 0x0000FF00u) << 8) | ((a[w] >> 8) & 0x0000FF00u);
+    else
+      a[w] = zc::permute_bytes(a[w], a[w], 0x03010200u);
+  }
+  // then 4 x 4, 2 x 2 and 1 x 1 blocks between words j apart; each mask's complement is the
+  // mask shifted up by j, so a result is one shift and one bit-field insert
   constexpr uint32_t mask[3] = {0x0F0F0F0Fu, 0x33333333u, 0x55555555u};
   int m = 0;
 #pragma unroll
@@ -81,7 +89,7 @@ ZC_DEV constexpr void transpose_halves(uint32_t (&a)[8]) {
     for (int w = 0; w < 8; ++w)
       if ((w & j) == 0) {
         const uint32_t lo = a[w], hi = a[w + j];
-        a[w] = (lo & mask[m]) | ((hi & mask[m]) << j);
+        a[w] = (lo & mask[m]) | ((hi << j) & ~mask[m]);
         a[w + j] = ((lo >> j) & mask[m]) | (hi & ~mask[m]);
       }
 }
@@ -101,21 +109,30 @@ constexpr ExpandTable build_expand_table() {
   return t;
 }
 
-// Decoder: entry for the next kLookahead stream bits at the start of a group test, when
-// `room` coefficients lie between the current one and the last (rows room = 0 ..
-// kLookahead-1, and one row for everything above, where the end cannot be reached within
-// the look-ahead).  It holds all the tokens that lie whole within those bits: group bit,
-// zeros, closing one; a run of `room` zeros reaches the last coefficient, whose one needs
-// no closing bit and after which the plane is done; a group bit 0 closes the plane.
-// Bits 0..9: the ones, as positions past the current coefficient; bits 12..15: how many
-// coefficients were passed; bits 16..19: how many stream bits were used (0: the first
-// token does not end within the look-ahead); bit 20: the plane is done.
+// Decoder: entry for the next kLookahead stream bits at the start of a group test, by how far
+// the last coefficient is.  The decoder keeps, per plane, a state s = (index of the first
+// coefficient not yet known to be significant) | (plane closed) << 5 and looks up row
+// clamp(s, 6, 16) - 6: row 0 serves the indices up to 6, from where the last coefficient
+// cannot be reached within the look-ahead; rows 1..9 are the indices 7..15 (8..0 coefficients
+// between the current one and the last); row 10, all zeros, is what a lane reads whose plane is
+// closed (a closing zero was read, or the last coefficient dealt with), so that it can step
+// along with the others and nothing happens.
+// An entry holds all the tokens that lie whole within the look-ahead: group bit, zeros,
+// closing one; a run that reaches the last coefficient needs no closing one, and the plane is
+// closed after it; a group bit 0 closes the plane.
+// Bits 0..9: the ones, as positions past the current coefficient; bits 10..14: how many
+// coefficients were passed; bit 15: the plane is closed (bits 10..15 are added to s);
+// bits 20..23: how many stream bits were used; bit 31: no token ends within the look-ahead
+// (so that entry >> 20 exceeds any budget, and the decoder reads one token on its own).
 constexpr int kLookahead = 9;
-constexpr int kTokenRows = kLookahead + 1;
+constexpr int kTokenRows = 11;
+constexpr uint32_t kTokenFirstRowState = 6, kTokenIdleState = 16;
 struct TokenTable { uint32_t v[kTokenRows << kLookahead]; };
 constexpr TokenTable build_token_table() {
   TokenTable t{};
-  for (uint32_t room = 0; room < (uint32_t)kTokenRows; ++room)
+  for (uint32_t row = 0; row + 1 < (uint32_t)kTokenRows; ++row) {
+    // coefficients between the current one and the last; row 0 stands for nine and more
+    const uint32_t room = row == 0 ? 15u : 9u - row;
     for (uint32_t s = 0; s < (1u << kLookahead); ++s) {
       uint32_t ones = 0, passed = 0, used = 0, done = 0;
       for (;;) {
@@ -134,8 +151,9 @@ constexpr TokenTable build_token_table() {
         used += 1 + z + (passed + z == room ? 0 : 1);       // no closing one at the last coefficient
         passed += z + 1;
       }
-      t.v[(room << kLookahead) + s] = ones | passed << 12 | used << 16 | done << 20;
+      t.v[(row << kLookahead) + s] = ones | passed << 10 | done << 15 | used << 20 | (used == 0u ? 1u << 31 : 0u);
     }
+  }
   return t;
 }
 
@@ -276,16 +294,19 @@ ZC_DEV void inverse_transform(uint32_t (&u)[16], uint32_t E, float (&out)[16]) {
 }
 
 // One plane of the embedded code, read from the bottom of the window W.  Returns the
-// plane's bit of each coefficient.
+// plane's bit of each coefficient.  n: how many leading coefficients are significant.
 //
 // The group tests are read in steps that all lanes of the wavefront take together.  A step
-// looks the next bits up in the token table; if in every lane that still reads this plane
-// the entry's tokens lie inside the budget, the step is just the entry applied (lanes that
-// are done apply an empty entry).  Otherwise (some lane's first token is longer than the
-// look-ahead, or its budget ends inside the entry's bits) the step takes the general form:
-// per lane the entry if it fits, else one token by count-trailing-zeros with the limits
-// applied.  Budgets of the lanes of a wavefront end within a few steps of each other, so the
-// general form is needed near a block's end only.
+// looks the next bits up in the token table (see there for the state s and the rows); if in
+// every lane that still reads this plane the entry's tokens lie inside the budget, the step is
+// just the entry applied: lanes whose plane is closed read empty entries, lanes out of budget
+// apply nothing.  Otherwise (some lane's first token is longer than the look-ahead, or its
+// budget ends inside the entry's bits) the step takes the general form: per lane the entry if
+// it fits, else one token by count-trailing-zeros with the limits applied.  Budgets of the
+// lanes of a wavefront end within a few steps of each other, so the general form is needed
+// near a block's end only.  any_lane_active.lanes(p) is the set of lanes where p holds, taken
+// per comparison (a compare instruction's result is that set), and .some(set) whether a set
+// is non-empty.
 template <int NW, class AnyActive>
 ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t& n, uint32_t& left,
                              AnyActive any_lane_active) {
@@ -293,39 +314,38 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
   uint32_t pat = W[0] & ((1u << vlen) - 1u);
   zc::shift_out<NW>(W, vlen);
   left -= vlen;
-  // i: first coefficient not yet known to be significant; closed: the plane's closing zero
-  // has been read or its last coefficient dealt with
-  uint32_t i = n, closed = n >> 4;
+  uint32_t s = n;   // n = 16: nothing left to test, the plane counts as closed
   for (;;) {
-    const bool active = closed == 0u && left > 0u;
-    if (!any_lane_active(active)) break;
-    // all the tokens that lie whole in the next bits
-    const uint32_t e = token[(umin(15u - i, (uint32_t)kLookahead) << kLookahead) + (W[0] & ((1u << kLookahead) - 1u))];
-    const uint32_t t_used = (e >> 16) & 15u;
-    const bool fits = t_used != 0u && t_used <= left;
-    if (!any_lane_active(active && !fits)) {
-      const uint32_t a = active ? e : 0u;
-      pat |= (a & 0x3FFu) << i;
-      i += (a >> 12) & 15u;
-      closed |= a >> 20;
-      const uint32_t used = (a >> 16) & 15u;
+    const bool open = s < kTokenIdleState, funded = left > 0u;
+    const auto reading = any_lane_active.lanes(open) & any_lane_active.lanes(funded);
+    if (!any_lane_active.some(reading)) break;
+    // byte offset of the entry: row (clamped state - first row's state), then the next bits
+    const uint32_t row = (umin(umax(s, kTokenFirstRowState), kTokenIdleState) << (kLookahead + 2)) -
+                         (kTokenFirstRowState << (kLookahead + 2));
+    const uint32_t e = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(token) +
+                                                          (row | (W[0] & ((1u << kLookahead) - 1u)) << 2));
+    const bool unfit = (e >> 20) > left;
+    if (!any_lane_active.some(reading & any_lane_active.lanes(unfit))) {
+      const uint32_t a = funded ? e : 0u;
+      pat |= (a & 0x3FFu) << (s & 31u);
+      s += (a >> 10) & 0x3Fu;
+      const uint32_t used = (a >> 20) & 15u;
       zc::shift_out<NW>(W, used);
       left -= used;
-    } else if (active) {
+    } else if (open && funded) {
       // one token with the limits applied where the entry does not fit (its group bit is a one,
       // or the table would have served): zeros up to the one; the run ends at the last
       // coefficient or at the budget
-      const uint32_t room = umin(15u - i, left - 1u);
+      const uint32_t room = umin(15u - s, left - 1u);
       const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
-      const uint32_t used = fits ? t_used : 1u + z + (z < room ? 1u : 0u);
-      pat |= (fits ? (e & 0x3FFu) : 1u << z) << i;
-      i += fits ? (e >> 12) & 15u : z + 1u;
-      closed |= (fits ? e >> 20 : 0u) | (i >> 4);
+      const uint32_t used = unfit ? 1u + z + (z < room ? 1u : 0u) : (e >> 20) & 15u;
+      pat |= (unfit ? 1u << z : e & 0x3FFu) << s;
+      s += unfit ? z + 1u : (e >> 10) & 0x3Fu;
       zc::shift_out<NW>(W, used);
       left -= used;
     }
   }
-  n = i;
+  n = s & 31u;
   return pat;
 }
 
@@ -365,6 +385,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
   transpose_halves(h);
 #pragma unroll
   for (int w = 0; w < 8; ++w) {
+    zc::materialise(h[w]);   // one transpose, not one per half
     u[w] = h[w] << 16;
     u[w + 8] = h[w] & 0xFFFF0000u;
   }
@@ -380,6 +401,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
     transpose_halves(h);
 #pragma unroll
     for (int w = 0; w < 8; ++w) {
+      zc::materialise(h[w]);
       u[w] |= h[w] & 0xFFFFu;
       u[w + 8] |= h[w] >> 16;
     }

@@ -33,8 +33,13 @@ __device__ __forceinline__ void stage_table(const uint32_t* __restrict__ src, ui
 // the compress kernel).  Only a build with -DZC_TUNING_KNOBS lets ZC2D_WORKGROUPS_PER_CU override both; the shipped library reads no environment variable.
 constexpr int kCompressWorkgroupsPerCU = 16, kDecodeWorkgroupsPerCU = 32;
 
+// The wavefront-wide votes of the codec: lanes(p) is the set of lanes where p holds (one
+// comparison each, so that the compare instruction's own mask is the set), some(set) whether
+// it is non-empty; any_lane_active(p) = some(lanes(p)).
 struct AnyLane {
-  __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
+  __device__ uint64_t lanes(bool p) const { return __builtin_amdgcn_ballot_w64(p); }
+  __device__ bool some(uint64_t set) const { return set != 0; }
+  __device__ bool operator()(bool p) const { return __builtin_amdgcn_ballot_w64(p) != 0; }
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -48,6 +48,17 @@ constexpr int kFractionBits = 28;
 
 // ---- small bit helpers -------------------------------------------------------------
 
+// Makes v opaque to the compiler at this point: it is computed once, as a whole, and what
+// follows starts from that register.  (Without it the compiler may split a computation by the
+// bits each later use needs and do much of it twice.)
+ZC_DEV void materialise(uint32_t& v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm("" : "+v"(v));
+#else
+  (void)v;
+#endif
+}
+
 // ({hi,lo} >> (s & 31)) truncated to 32 bits.
 ZC_DEV uint32_t alignbit(uint32_t hi, uint32_t lo, uint32_t s) {
 #if defined(__HIP_DEVICE_COMPILE__)

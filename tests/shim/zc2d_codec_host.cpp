@@ -9,7 +9,13 @@
 #include "../../paper_2409_02423_amd/csrc/zc2d_codec.h"
 
 namespace {
-auto always = [](bool p) { return p; };
+// one lane alone: the set of lanes where p holds is p itself
+struct Alone {
+  bool lanes(bool p) const { return p; }
+  bool some(bool set) const { return set; }
+  bool operator()(bool p) const { return p; }
+};
+const Alone always;
 constexpr zc2d::ExpandTable kExpand = zc2d::build_expand_table();
 constexpr zc2d::TokenTable kToken = zc2d::build_token_table();
 
@@ -59,7 +65,14 @@ template <int RATE>
 void wave(bool encode, const uint8_t* in, size_t blocks, uint8_t* out, int lanes) {
   constexpr int B = zc2d::Traits<RATE>::kBlockBytes;
   Ballot ballot(lanes);
-  auto vote = [&ballot](bool p) { return ballot.vote(p); };
+  // a thread's share of a set of lanes is its own predicate; the vote joins them
+  struct Vote {
+    Ballot* b;
+    bool lanes(bool p) const { return p; }
+    bool some(bool set) const { return b->vote(set); }
+    bool operator()(bool p) const { return b->vote(p); }
+  };
+  const Vote vote{&ballot};
   const size_t waves = (blocks + lanes - 1) / lanes;
   std::vector<std::thread> pool;
   for (int t = 0; t < lanes; ++t)
