@@ -255,7 +255,7 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32
   uint32_t n = 0;
   uint32_t h[8];
 #pragma unroll
-  for (int w = 0; w < 8; ++w) h[w] = (u[w] >> 16) | (u[w + 8] & 0xFFFF0000u);
+  for (int w = 0; w < 8; ++w) h[w] = zc::permute_bytes(u[w + 8], u[w], 0x07060302u);   // the two upper halves
   transpose_halves(h);
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
@@ -265,7 +265,7 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32
   }
   if (kMaxPlanes > 16 && any_lane_active(left > 0)) {
 #pragma unroll
-    for (int w = 0; w < 8; ++w) h[w] = (u[w] & 0xFFFFu) | (u[w + 8] << 16);
+    for (int w = 0; w < 8; ++w) h[w] = zc::permute_bytes(u[w + 8], u[w], 0x05040100u);   // the two lower halves
     transpose_halves(h);
 #pragma unroll
     for (int t = 16; t < 32; ++t) {
@@ -372,6 +372,8 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
   uint32_t left = (uint32_t)kPayload - lead;
   if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
   zc::shift_right<NW>(W, lead + 8u);
+  // a lane whose planes start more than 16 below the top (and that has any to read)
+  const bool low_start = lead > 16u && left > 0u;
   uint32_t n = 0;
   uint32_t h[8], u[16];
 #pragma unroll
@@ -384,30 +386,43 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
   }
   transpose_halves(h);
 #pragma unroll
-  for (int w = 0; w < 8; ++w) {
-    zc::materialise(h[w]);   // one transpose, not one per half
-    u[w] = h[w] << 16;
-    u[w + 8] = h[w] & 0xFFFF0000u;
-  }
-  if (kMaxPlanes > 16 && any_lane_active(left > 0)) {
-#pragma unroll
-    for (int w = 0; w < 8; ++w) h[w] = 0u;
-#pragma unroll
-    for (int t = 16; t < 32; ++t) {
-      if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
-      const int b = 31 - t;
-      h[b & 7] |= decode_plane<NW>(token, W, n, left, any_lane_active) << (16 * (b >> 3));
-    }
-    transpose_halves(h);
+  for (int w = 0; w < 8; ++w) zc::materialise(h[w]);   // one transpose, not one per half
+  const bool deeper = kMaxPlanes > 16 && any_lane_active(left > 0);
+  if (!deeper && !any_lane_active(low_start)) {
+    // the usual case: at most 16 planes were read and they start within the top 16, so each
+    // coefficient is its 16-bit pattern moved up (a lane that read nothing has zero patterns)
+    const uint32_t up = (16u - lead) & 31u;
 #pragma unroll
     for (int w = 0; w < 8; ++w) {
-      zc::materialise(h[w]);
-      u[w] |= h[w] & 0xFFFFu;
-      u[w + 8] |= h[w] >> 16;
+      u[w] = (h[w] & 0xFFFFu) << up;
+      u[w + 8] = (h[w] >> 16) << up;
     }
-  }
+  } else {
 #pragma unroll
-  for (int c = 0; c < 16; ++c) u[c] >>= (lead & 31u);   // nothing was decoded if lead >= 32
+    for (int w = 0; w < 8; ++w) {
+      u[w] = h[w] << 16;
+      u[w + 8] = h[w] & 0xFFFF0000u;
+    }
+    if (deeper) {
+#pragma unroll
+      for (int w = 0; w < 8; ++w) h[w] = 0u;
+#pragma unroll
+      for (int t = 16; t < 32; ++t) {
+        if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
+        const int b = 31 - t;
+        h[b & 7] |= decode_plane<NW>(token, W, n, left, any_lane_active) << (16 * (b >> 3));
+      }
+      transpose_halves(h);
+#pragma unroll
+      for (int w = 0; w < 8; ++w) {
+        zc::materialise(h[w]);
+        u[w] |= h[w] & 0xFFFFu;
+        u[w + 8] |= h[w] >> 16;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) u[c] >>= (lead & 31u);   // nothing was decoded if lead >= 32
+  }
   inverse_transform(u, E, out);
 }
 
