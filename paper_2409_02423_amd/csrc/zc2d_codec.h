@@ -69,12 +69,16 @@ constexpr Order kOrder = build_order();
 // ---- 16 x 16 bit transpose on eight words ----------------------------------------------
 // Row r of a 16 x 16 bit matrix sits in half r >> 3 of word r & 7 (half 0 = bits 0..15).
 // The transpose leaves the matrix in the same arrangement, so it is its own inverse.
+// WHOLE: all eight results are needed (the decoder), so the byte swap is one permute per word;
+// otherwise plain bit operations throughout, which lets the compiler compute only what the
+// planes actually coded ask for (the encoder, which at low rates codes few of the 16).
+template <bool WHOLE>
 ZC_DEV constexpr void transpose_halves(uint32_t (&a)[8]) {
   // swap the 8 x 8 quadrants: bits 8..15 of row r with bits 0..7 of row r + 8 (the two middle
   // bytes of each word change places)
 #pragma unroll
   for (int w = 0; w < 8; ++w) {
-    if (__builtin_is_constant_evaluated())
+    if (!WHOLE || __builtin_is_constant_evaluated())
       a[w] = (a[w] & 0xFF0000FFu) | ((a[w] & 0x0000FF00u) << 8) | ((a[w] >> 8) & 0x0000FF00u);
     else
       a[w] = zc::permute_bytes(a[w], a[w], 0x03010200u);
@@ -158,6 +162,7 @@ constexpr TokenTable build_token_table() {
 }
 
 namespace selfcheck {
+template <bool WHOLE>
 constexpr bool transpose_ok() {
   uint32_t a[8] = {}, ref[8] = {};
   uint32_t s = 0x9E3779B9u;
@@ -165,12 +170,12 @@ constexpr bool transpose_ok() {
   for (int r = 0; r < 16; ++r)
     for (int b = 0; b < 16; ++b)
       ref[b & 7] |= ((a[r & 7] >> (16 * (r >> 3) + b)) & 1u) << (16 * (b >> 3) + r);
-  transpose_halves(a);
+  transpose_halves<WHOLE>(a);
   for (int w = 0; w < 8; ++w)
     if (a[w] != ref[w]) return false;
   return true;
 }
-static_assert(transpose_ok(), "16 x 16 bit transpose");
+static_assert(transpose_ok<true>() && transpose_ok<false>(), "16 x 16 bit transpose");
 }  // namespace selfcheck
 
 // ---- forward ---------------------------------------------------------------------------
@@ -255,8 +260,8 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32
   uint32_t n = 0;
   uint32_t h[8];
 #pragma unroll
-  for (int w = 0; w < 8; ++w) h[w] = zc::permute_bytes(u[w + 8], u[w], 0x07060302u);   // the two upper halves
-  transpose_halves(h);
+  for (int w = 0; w < 8; ++w) h[w] = (u[w] >> 16) | (u[w + 8] & 0xFFFF0000u);
+  transpose_halves<false>(h);
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
     if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
@@ -265,8 +270,8 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32
   }
   if (kMaxPlanes > 16 && any_lane_active(left > 0)) {
 #pragma unroll
-    for (int w = 0; w < 8; ++w) h[w] = zc::permute_bytes(u[w + 8], u[w], 0x05040100u);   // the two lower halves
-    transpose_halves(h);
+    for (int w = 0; w < 8; ++w) h[w] = (u[w] & 0xFFFFu) | (u[w + 8] << 16);
+    transpose_halves<false>(h);
 #pragma unroll
     for (int t = 16; t < 32; ++t) {
       if (t >= kMaxPlanes || !any_lane_active(left > 0)) break;
@@ -280,18 +285,37 @@ ZC_DEV void encode_block(const uint32_t (&x)[16], const uint32_t* expand, uint32
 
 // ---- inverse -----------------------------------------------------------------------------
 
-ZC_DEV void inverse_transform(uint32_t (&u)[16], uint32_t E, float (&out)[16]) {
-  int32_t q[16];
+// Negabinary words in coefficient order -> the block's fixed-point values, row-major.
+ZC_DEV void inverse_transform(uint32_t (&u)[16], int32_t (&q)[16]) {
 #pragma unroll
   for (int c = 0; c < 16; ++c) q[kOrder.v[c]] = zc::negabinary_to_int(u[c]);
 #pragma unroll
   for (int c = 0; c < 4; ++c) zc::inverse_lift(q[c], q[4 + c], q[8 + c], q[12 + c]);
 #pragma unroll
   for (int r = 0; r < 4; ++r) zc::inverse_lift(q[4 * r], q[4 * r + 1], q[4 * r + 2], q[4 * r + 3]);
+}
+
+// Fixed-point values -> fp32: int -> fp32 rounds to nearest even, the scaling by
+// 2^(E - 127 - 27) is exact and rounds once more only for subnormal results.
+ZC_DEV void scale_block(const int32_t (&q)[16], uint32_t E, float (&out)[16]) {
   const int ex = (int)E - 127 - kFractionBits;
 #pragma unroll
   for (int i = 0; i < 16; ++i) out[i] = __builtin_ldexpf((float)q[i], ex);
 }
+
+// sum += the block's fp32 values, for exponent bytes where the scaling is exact and finite
+// (see scaling_is_exact): the product of the rounded integer and the power of two is then the
+// decoded value itself, and the fused multiply-add rounds the sum once, as the addition would.
+ZC_DEV void accumulate_scaled(const int32_t (&q)[16], uint32_t E, float (&sum)[16]) {
+  const float scale = __builtin_ldexpf(1.0f, (int)E - 127 - kFractionBits);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum[i] = __builtin_fmaf((float)q[i], scale, sum[i]);
+}
+
+// Nonzero values have magnitude 1 .. 2^31 before scaling: from E = 28 on none of them becomes
+// subnormal, up to E = 250 none overflows.  In the zero block (E = 0) all values are zero, and
+// zero times anything finite added to the sum is the sum plus zero.
+ZC_DEV bool scaling_is_exact(uint32_t E) { return E - 28u <= 222u || E == 0u; }
 
 // One plane of the embedded code, read from the bottom of the window W.  Returns the
 // plane's bit of each coefficient.  n: how many leading coefficients are significant.
@@ -349,9 +373,10 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
   return pat;
 }
 
+// Whole block up to the fixed-point values; returns the exponent byte.
 template <int RATE, class AnyActive>
-ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* token, float (&out)[16],
-                         AnyActive any_lane_active) {
+ZC_DEV uint32_t decode_block_fixed(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* token, int32_t (&q)[16],
+                                   AnyActive any_lane_active) {
   constexpr int NW = Traits<RATE>::kWords;
   constexpr int kPayload = Traits<RATE>::kPayloadBits;
   constexpr int kMaxPlanes = kPayload < 32 ? kPayload : 32;
@@ -384,7 +409,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
     const int b = 15 - t;
     h[b & 7] |= decode_plane<NW>(token, W, n, left, any_lane_active) << (16 * (b >> 3));
   }
-  transpose_halves(h);
+  transpose_halves<true>(h);
 #pragma unroll
   for (int w = 0; w < 8; ++w) zc::materialise(h[w]);   // one transpose, not one per half
   const bool deeper = kMaxPlanes > 16 && any_lane_active(left > 0);
@@ -412,7 +437,7 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
         const int b = 31 - t;
         h[b & 7] |= decode_plane<NW>(token, W, n, left, any_lane_active) << (16 * (b >> 3));
       }
-      transpose_halves(h);
+      transpose_halves<true>(h);
 #pragma unroll
       for (int w = 0; w < 8; ++w) {
         zc::materialise(h[w]);
@@ -423,7 +448,16 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* to
 #pragma unroll
     for (int c = 0; c < 16; ++c) u[c] >>= (lead & 31u);   // nothing was decoded if lead >= 32
   }
-  inverse_transform(u, E, out);
+  inverse_transform(u, q);
+  return E;
+}
+
+template <int RATE, class AnyActive>
+ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const uint32_t* token, float (&out)[16],
+                         AnyActive any_lane_active) {
+  int32_t q[16];
+  const uint32_t E = decode_block_fixed<RATE>(W, token, q, any_lane_active);
+  scale_block(q, E, out);
 }
 
 }  // namespace zc2d

@@ -266,11 +266,19 @@ __global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chun
 #pragma unroll 1
     for (int j = 1; j < k; ++j) {
       uint32_t W[NW];
-      float y[16];
+      int32_t q[16];
       load_words<NW>(chunks.p[j] + at, W);
-      zc2d::decode_block<RATE>(W, token, y, AnyLane());
+      const uint32_t E = zc2d::decode_block_fixed<RATE>(W, token, q, AnyLane());
+      // scale and add in one fused step, unless some lane's exponent byte is one where the
+      // scaling may round or overflow (tiny or huge blocks, arbitrary bytes)
+      if (AnyLane()(!zc2d::scaling_is_exact(E))) {
+        float y[16];
+        zc2d::scale_block(q, E, y);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sum[i] += y[i];
+        for (int i = 0; i < 16; ++i) sum[i] += y[i];
+      } else {
+        zc2d::accumulate_scaled(q, E, sum);
+      }
     }
     if constexpr (LOCAL) {
       // (where the block sticks out of the matrix the clamped loads add copies of edge values;

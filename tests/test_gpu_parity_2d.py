@@ -195,6 +195,43 @@ def test_reduce_matches_reference(gpu, ref, rate):
         _same_bytes(_host(acc), ref.reduce_compressed(comp[:2], rows, cols, rate), rate, "reduce in place")
 
 
+@pytest.mark.parametrize("rate", RATES)
+def test_reduce_on_arbitrary_bytes(gpu, ref, rate):
+    """The three reduce calls on streams of arbitrary bytes, with plenty of exponent bytes at both
+    ends of the range (where the scaling of a decoded value rounds to a subnormal or overflows,
+    and the kernel's fused scale-and-add must give way to decode-then-add): fp32 sums equal the
+    reference's wherever they are not NaN, stream bytes wherever the block's sums are finite."""
+    print("2d reduce on arbitrary bytes, rate", rate, flush=True)
+    rng = np.random.default_rng(700 + rate)
+    rows, cols = 64, 320
+    size = ref.compressed_size(rows, cols, rate)
+    streams = [rng.integers(0, 256, size=size, dtype=np.uint8) for _ in range(3)]
+    streams[1][: size // 2] &= rng.integers(0, 256, size=size // 2, dtype=np.uint8)
+    for s in streams:
+        hdr = s[:: 2 * rate]
+        sel = rng.random(hdr.size)
+        hdr[sel < 0.05] = rng.integers(248, 256, size=int((sel < 0.05).sum()), dtype=np.uint8)
+        hdr[sel > 0.90] = rng.integers(0, 40, size=int((sel > 0.90).sum()), dtype=np.uint8)
+    local = (workloads.gradient_iid(rows * cols) * np.float32(1e30)).reshape(rows, cols)
+    dstreams = [_dev(s) for s in streams]
+    for k, loc in ((2, None), (3, None), (1, local), (3, local)):
+        with np.errstate(all="ignore"):
+            sums = ref.reduce_decompress(streams[:k], loc, rows, cols, rate)
+            want_c = ref.reduce_mixed(streams[:k], loc, rows, cols, rate)
+        dloc = None if loc is None else _dev(loc)
+        got_raw = _host(gpu.zc2d_reduce_decompress(dstreams[:k], dloc, rows, cols, rate))
+        got_c = _host(gpu.zc2d_reduce_mixed(dstreams[:k], dloc, rows, cols, rate)) if loc is not None else \
+            _host(gpu.zc2d_reduce_compressed(dstreams[:k], rows, cols, rate))
+        not_nan = ~np.isnan(sums)
+        assert np.isinf(sums).sum() > 50 and (~not_nan).sum() < sums.size // 4
+        _same_floats(got_raw[not_nan], sums[not_nan], "2d reduce_decompress arbitrary bytes r%d k%d" % (rate, k))
+        assert np.isnan(got_raw[~not_nan]).all()
+        finite = np.isfinite(sums).reshape(rows // 4, 4, cols // 4, 4).all(axis=(1, 3)).reshape(-1)
+        assert finite.sum() > 0.7 * finite.size
+        per_byte = np.repeat(finite, 2 * rate)
+        _same_bytes(got_c[per_byte], want_c[per_byte], rate, "2d reduce arbitrary bytes r%d k%d" % (rate, k))
+
+
 @pytest.mark.parametrize("name", ["bf16", "f16"])
 def test_half_precision_matrices(gpu, ref, name):
     import torch
