@@ -343,11 +343,17 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
     const bool open = s < kTokenIdleState, funded = left > 0u;
     const auto reading = any_lane_active.lanes(open) & any_lane_active.lanes(funded);
     if (!any_lane_active.some(reading)) break;
-    // byte offset of the entry: row (clamped state - first row's state), then the next bits
-    const uint32_t row = (umin(umax(s, kTokenFirstRowState), kTokenIdleState) << (kLookahead + 2)) -
-                         (kTokenFirstRowState << (kLookahead + 2));
-    const uint32_t e = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(token) +
-                                                          (row | (W[0] & ((1u << kLookahead) - 1u)) << 2));
+    // byte offset of the entry: (clamped state - first row's state) rows, then the next bits;
+    // the constant rides on the masking of the bits (it has none of their positions set)
+    constexpr uint32_t kRowBytesLg = kLookahead + 2;
+    constexpr uint32_t kBias = 0u - (kTokenFirstRowState << kRowBytesLg);
+    const uint32_t clamped = umin(umax(s, kTokenFirstRowState), kTokenIdleState);
+    uint32_t bits = W[0] & ((1u << kLookahead) - 1u);
+    zc::materialise(bits);   // (a bit-field extract, then shift-and-or with the constant, then shift-and-add:
+    bits = bits << 2 | kBias;   //  otherwise the constant comes back as an addition of its own)
+    zc::materialise(bits);
+    const uint32_t at = (clamped << kRowBytesLg) + bits;
+    const uint32_t e = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(token) + at);
     const bool unfit = (e >> 20) > left;
     if (!any_lane_active.some(reading & any_lane_active.lanes(unfit))) {
       const uint32_t a = funded ? e : 0u;
@@ -359,12 +365,16 @@ ZC_DEV uint32_t decode_plane(const uint32_t* token, uint32_t (&W)[NW], uint32_t&
     } else if (open && funded) {
       // one token with the limits applied where the entry does not fit (its group bit is a one,
       // or the table would have served): zeros up to the one; the run ends at the last
-      // coefficient or at the budget
+      // coefficient or at the budget.  (The entry is taken up afresh here, so that nothing of
+      // this rare form is computed ahead of the branch.)
+      uint32_t f = e;
+      zc::materialise(f);
+      const bool cut = (f >> 20) > left;
       const uint32_t room = umin(15u - s, left - 1u);
       const uint32_t z = umin(count_trailing_zeros(W[0] >> 1), room);
-      const uint32_t used = unfit ? 1u + z + (z < room ? 1u : 0u) : (e >> 20) & 15u;
-      pat |= (unfit ? 1u << z : e & 0x3FFu) << s;
-      s += unfit ? z + 1u : (e >> 10) & 0x3Fu;
+      const uint32_t used = cut ? 1u + z + (z < room ? 1u : 0u) : (f >> 20) & 15u;
+      pat |= (cut ? 1u << z : f & 0x3FFu) << s;
+      s += cut ? z + 1u : (f >> 10) & 0x3Fu;
       zc::shift_out<NW>(W, used);
       left -= used;
     }

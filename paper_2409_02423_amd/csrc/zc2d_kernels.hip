@@ -242,9 +242,11 @@ struct ChunkPointers2d {
 // block sticks out of the matrix its fill is taken from the sum's last valid row / column.
 // LOCAL: a raw fp32 matrix is added last (a ring hop's own contribution); RAW_OUT: the sum
 // is stored as an fp32 matrix instead of being encoded (the last hop).
+// (The plain form at the low rates is two registers away from a sixth wavefront per SIMD, which
+// it gains from: the compiler is told to stay within that; the other forms would spill.)
 template <int RATE, bool LOCAL, bool RAW_OUT>
-__global__ __launch_bounds__(kThreads) void reduce2d_kernel(ChunkPointers2d chunks, int k, const float* local, Walk w,
-                                                            uint8_t* out, float* out_raw) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(RATE <= 4 && !LOCAL && !RAW_OUT ? 6 : 1)))
+void reduce2d_kernel(ChunkPointers2d chunks, int k, const float* local, Walk w, uint8_t* out, float* out_raw) {
   __shared__ __attribute__((aligned(16))) uint32_t expand[256];
   __shared__ __attribute__((aligned(16))) uint32_t token[zc2d::kTokenRows << zc2d::kLookahead];
   for (int i = threadIdx.x; i < 256 / 4; i += kThreads)
