@@ -435,7 +435,9 @@ ZC_DEV void forward_transform(const uint32_t (&x)[4], uint32_t& E, uint32_t (&u)
 
 // Whole block: exponent byte + embedded code of the coefficients, cut at the budget.
 // `any_lane_active(pred)` tells whether any lane of the wavefront still has pred set
-// (loop control only).
+// (loop control only); any_lane_active.lanes(pred) is the set of those lanes and
+// any_lane_active.some(set) whether a set is non-empty, for votes on several comparisons
+// at once (each comparison's own result is such a set, and sets combine for free).
 //
 // Rates above 4 encode in two phases, around the block's literal plane string: the planes
 // from the first non-empty one down, four bits each in coefficient order, which is what
@@ -500,14 +502,14 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
 #pragma unroll
     for (int w = 0; w < kLitWords; ++w) {
       if (open) {
-        if (w > 0 && any_lane_active(left > 0 && state < 3u * 256u * 4u)) {
+        if (w > 0 && any_lane_active.some(any_lane_active.lanes(left > 0) & any_lane_active.lanes(state < 3u * 256u * 4u))) {
           make_word(w);
           made = w + 1;
         }
         uint32_t z = lit[w], s = 0;
 #pragma unroll 1
         for (; s < 4u; ++s) {
-          if (!any_lane_active(left > 0 && state < 3u * 256u * 4u)) break;
+          if (!any_lane_active.some(any_lane_active.lanes(left > 0) & any_lane_active.lanes(state < 3u * 256u * 4u))) break;
           const uint32_t e = tab.enc[(state >> 2) + (z & 0xFFu)];
           z >>= 8;
           const uint32_t len = umin((e >> 14) & 15u, left);
@@ -658,10 +660,10 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
       uint32_t s = 0;
 #pragma unroll 1
       for (; s < 4u; ++s) {
-        const bool reading = state < kDecIdle;
-        if (!any_lane_active(reading)) break;
+        const auto reading = any_lane_active.lanes(state < kDecIdle);
+        if (!any_lane_active.some(reading)) break;
         uint32_t e;
-        if (any_lane_active(reading && left < (uint32_t)kDecLook)) {
+        if (any_lane_active.some(reading & any_lane_active.lanes(left < (uint32_t)kDecLook))) {
           const uint32_t mask = (1u << umin(left, 7u)) - 1u;
           e = tab.dec[kDecLookEntries + (state >> 3) + mask + ((W[0] >> 2) & mask)];
         } else {

@@ -31,7 +31,9 @@ constexpr int kMaxChunks = 16;
 constexpr size_t kWideBlocks = 512;     // blocks per wavefront and pass of the wide rate-4 kernels
 
 struct AnyLane {
-  __device__ bool operator()(bool pred) const { return __builtin_amdgcn_ballot_w64(pred) != 0; }
+  __device__ uint64_t lanes(bool p) const { return __builtin_amdgcn_ballot_w64(p); }
+  __device__ bool some(uint64_t set) const { return set != 0; }
+  __device__ bool operator()(bool p) const { return __builtin_amdgcn_ballot_w64(p) != 0; }
 };
 
 // Copy a code table into LDS: every thread issues all of its 16-byte loads back to back.

@@ -16,7 +16,13 @@ const zc::Dec4Table kDec4 = zc::build_dec4_table();
 alignas(4) const zc::Enc4Table kEnc4 = zc::build_enc4_table();
 const zc::Tables kTables = {kEnc.v, kDec.v, kDec4.v};
 const zc::Tables kTables4 = {reinterpret_cast<const uint32_t*>(kEnc4.v), kDec.v, kDec4.v};
-auto always = [](bool p) { return p; };
+// one lane alone: the set of lanes where p holds is p itself
+struct Alone {
+  bool lanes(bool p) const { return p; }
+  bool some(bool set) const { return set; }
+  bool operator()(bool p) const { return p; }
+};
+const Alone always;
 
 template <int RATE>
 void enc(const float* x, uint8_t* out) {
@@ -66,7 +72,14 @@ template <int RATE>
 void wave(bool encode, const uint8_t* in, size_t blocks, uint8_t* out, int lanes) {
   constexpr int B = zc::Traits<RATE>::kBlockBytes;
   Ballot ballot(lanes);
-  auto vote = [&ballot](bool p) { return ballot.vote(p); };
+  // a thread's share of a set of lanes is its own predicate; the vote joins them
+  struct Vote {
+    Ballot* b;
+    bool lanes(bool p) const { return p; }
+    bool some(bool set) const { return b->vote(set); }
+    bool operator()(bool p) const { return b->vote(p); }
+  };
+  const Vote vote{&ballot};
   const size_t waves = (blocks + lanes - 1) / lanes;
   std::vector<std::thread> pool;
   for (int t = 0; t < lanes; ++t)
