@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restri
   constexpr int NW = zc::Traits<RATE>::kWords;
   constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
-  const size_t tiles = whole / kTile;
+  const size_t tiles = whole / kTile;   // below 2^30 (n is at most 2^40): tile numbers compare as 32-bit values, on the scalar side
   size_t t = blockIdx.x;
   if (t < tiles) {
     uint32_t x[U][4];
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restri
     for (int u = 0; u < U; ++u) load_values<DT>(in, t * kTile + u * kThreads + threadIdx.x, x[u]);
     while (true) {
       const size_t tn = t + gridDim.x;
-      const bool more = tn < tiles;   // the same in every lane of the workgroup
+      const bool more = (uint32_t)tn < (uint32_t)tiles;   // the same in every lane of the workgroup
       uint32_t xn[U][4];
       if (more) {
 #pragma unroll
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
   constexpr int NW = zc::Traits<RATE>::kWords;
   constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
-  const size_t tiles = whole / kTile;
+  const size_t tiles = whole / kTile;   // below 2^30 (n is at most 2^40): tile numbers compare as 32-bit values, on the scalar side
   size_t t = blockIdx.x;
   if (t < tiles) {
     uint32_t W[U][NW];
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const uint8_t* __r
     for (int u = 0; u < U; ++u) load_stream<RATE>(in, t * kTile + u * kThreads + threadIdx.x, W[u]);
     while (true) {
       const size_t tn = t + gridDim.x;
-      const bool more = tn < tiles;   // the same in every lane of the workgroup
+      const bool more = (uint32_t)tn < (uint32_t)tiles;   // the same in every lane of the workgroup
       uint32_t Wn[U][NW];
       if (more) {
 #pragma unroll
@@ -443,7 +443,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
   constexpr int NW = zc::Traits<RATE>::kWords;
   constexpr size_t kTile = (size_t)U * kThreads;
   const size_t whole = n / 4;
-  const size_t tiles = whole / kTile;
+  const size_t tiles = whole / kTile;   // below 2^30 (n is at most 2^40): tile numbers compare as 32-bit values, on the scalar side
 
   // s: the sum of one block; finishes it (local add, then encode or store)
   auto finish = [&](float (&s)[4], const uint32_t (&loc)[4], size_t j) {
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
     for (int u = 0; u < U; ++u) load_stream<RATE>(chunks.p[0], t * kTile + u * kThreads + threadIdx.x, W[u]);
     while (true) {
       const size_t tn = t + gridDim.x;
-      const bool more = tn < tiles;
+      const bool more = (uint32_t)tn < (uint32_t)tiles;
       uint32_t loc[U][4];
       if constexpr (LOCAL) {
 #pragma unroll
