@@ -406,7 +406,10 @@ ZC_DEV uint32_t decode_block_fixed(uint32_t (&W)[Traits<RATE>::kWords], const ui
   lead = umin(lead, (uint32_t)kPayload);
   uint32_t left = (uint32_t)kPayload - lead;
   if (E == 0u || (kPayload > 32 && lead >= 32u)) left = 0u;
-  zc::shift_right<NW>(W, lead + 8u);
+  // past the header byte and the leading zeros: two shifts of less than 32 each (with 32 and
+  // more leading zeros nothing is read from the window, whatever it holds)
+  zc::shift_out<NW>(W, 8u);
+  zc::shift_out<NW>(W, lead & 31u);
   // a lane whose planes start more than 16 below the top (and that has any to read)
   const bool low_start = lead > 16u && left > 0u;
   uint32_t n = 0;

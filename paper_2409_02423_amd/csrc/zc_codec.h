@@ -641,8 +641,11 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
     }
     lead = umin(lead, (uint32_t)kPayload);
     uint32_t left = (uint32_t)kPayload - lead;
-    // keep the next stream bit at bit 2 of the window: bits 10..2 index the look-ahead table directly
-    shift_right<NW>(W, lead + 6u);
+    // keep the next stream bit at bit 2 of the window: bits 10..2 index the look-ahead table directly.
+    // Two shifts of less than 32 each (a block with 32 and more leading empty planes has its
+    // window cleared below, so there only the low five bits of the count need to act).
+    shift_out<NW>(W, 6u);
+    shift_out<NW>(W, lead & 31u);
     uint32_t state = 0;
     // a zero block ignores its payload; after 32 empty planes nothing is left to decode
     if (E == 0u || (kPayload > 32 && lead >= 32u)) {
