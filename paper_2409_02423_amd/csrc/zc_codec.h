@@ -665,13 +665,16 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
       for (; s < 4u; ++s) {
         const auto reading = any_lane_active.lanes(state < kDecIdle);
         if (!any_lane_active.some(reading)) break;
-        uint32_t e;
+        // byte offset of the entry (the state code is the row's byte offset in the look-ahead
+        // table, eight times the row's in the budget table; the next stream bit is bit 2 of W[0])
+        uint32_t at;
         if (any_lane_active.some(reading & any_lane_active.lanes(left < (uint32_t)kDecLook))) {
-          const uint32_t mask = (1u << umin(left, 7u)) - 1u;
-          e = tab.dec[kDecLookEntries + (state >> 3) + mask + ((W[0] >> 2) & mask)];
+          const uint32_t mask4 = (4u << umin(left, 7u)) - 4u;   // the next min(left, 7) stream bits, in place
+          at = 4u * kDecLookEntries + (state >> 1) + mask4 + (W[0] & mask4);
         } else {
-          e = tab.dec[(state | (W[0] & (((1u << kDecLook) - 1u) << 2))) >> 2];
+          at = state | (W[0] & (((1u << kDecLook) - 1u) << 2));
         }
+        const uint32_t e = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(tab.dec) + at);
         const uint32_t planes = (e >> 2) & 3u, used = (e >> 4) & 15u;
         acc = (acc << planes) | (e & 0x03030303u);
         mg += planes;
