@@ -510,7 +510,9 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
 #pragma unroll 1
         for (; s < 4u; ++s) {
           if (!any_lane_active.some(any_lane_active.lanes(left > 0) & any_lane_active.lanes(state < 3u * 256u * 4u))) break;
-          const uint32_t e = tab.enc[(state >> 2) + (z & 0xFFu)];
+          uint32_t byte = z & 0xFFu;
+          materialise(byte);   // (so that the address is this byte shifted and added to the row's offset in one instruction)
+          const uint32_t e = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(tab.enc) + state + (byte << 2));
           z >>= 8;
           const uint32_t len = umin((e >> 14) & 15u, left);
           shift_in<NW>(P, e, len);  // only the low `len` bits of e enter the window
