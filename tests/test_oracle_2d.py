@@ -329,7 +329,13 @@ def test_half_precision_matrices_are_compositions(o2, oracle, name):
     """Widening (pinned against numpy in the 1-D tests) then the fp32 codec; the fp32 decoder then
     narrowing with numpy's own round-to-nearest-even cast (fp16) or the closed form on bits (bf16)."""
     from paper_2409_02423_amd import workloads
-    rows, cols = 37, 54
+    for rows, cols in ((37, 54), (38, 53), (4, 8)):
+        _half_matrix_case(o2, name, rows, cols)
+    with pytest.raises(ValueError):
+        o2.compress_half(np.zeros((4, 4), np.uint16), 0, 4)
+
+
+def _half_matrix_case(o2, name, rows, cols):
     f = (workloads.activation_gelu(rows * cols, config=3, index=4) * np.float32(2.5)).reshape(rows, cols)
     if name == "f16":
         bits, code = f.astype(np.float16).view(np.uint16), o2.F16
@@ -347,11 +353,9 @@ def test_half_precision_matrices_are_compositions(o2, oracle, name):
             u = d.view(np.uint32).astype(np.uint64)
             want = ((u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)).astype(np.uint16)
         assert np.array_equal(o2.decompress_half(s, rows, cols, rate, code), want), (name, rate)
-    with pytest.raises(ValueError):
-        o2.compress_half(bits, 0, 4)
 
 
-@pytest.mark.parametrize("shape", [(8, 12), (7, 10), (2, 3)])
+@pytest.mark.parametrize("shape", [(8, 12), (7, 10), (2, 3), (5, 9), (9, 5), (1, 1)])
 def test_ring_hop_variants_are_compositions(o2, shape):
     """reduce_mixed = compress(sum of decoded inputs + raw local matrix), reduce_decompress = that
     sum itself, both spelled out with numpy fp32 adds in the stated order."""
@@ -369,3 +373,66 @@ def test_ring_hop_variants_are_compositions(o2, shape):
             assert np.array_equal(o2.reduce_decompress(comp, None, rows, cols, rate).view(np.uint32), total.view(np.uint32))
             assert np.array_equal(o2.reduce_mixed(comp, local, rows, cols, rate), o2.compress(with_local, rate))
             assert np.array_equal(o2.reduce_mixed(comp, None, rows, cols, rate), o2.reduce_compressed(comp, rows, cols, rate))
+
+
+def _dense_blocks(count, seed):
+    """Blocks in which all coefficients become significant early, so that the stream carries
+    information up to its last bit."""
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((count, 16)) * rng.choice([1e-3, 1.0, 300.0], size=(count, 1))).astype(np.float32)
+
+
+@pytest.mark.parametrize("rate", [1, 2, 4, 8, 16, 32])
+def test_block_layout_and_budget(o2, oracle, rate):
+    """A block is 16*rate bits: the exponent byte, then the first 16*rate - 8 bits of the embedded
+    code of the 16 negabinary coefficients in sequency order, bit t of the code at bit 8 + t of
+    the block, least significant bit of each byte first.  Checked by building blocks from the
+    pinned stages, and by two properties that hold only if the budget is exactly that: the last
+    bit of the block is used by the encoder (it is a one in some blocks) and by the decoder
+    (flipping it changes some decoded block), while the decoder reads nothing past it."""
+    budget = 16 * rate - 8
+    order = o2.order()
+    last_bit_set = 0
+    last_bit_read = 0
+    for x in _dense_blocks(40, 900 + rate):
+        blk = o2.encode_block(x, rate)
+        assert blk.size == 2 * rate
+        E = o2.block_exponent(x)
+        q = o2.fwd_transform(o2.quantise(x, E))
+        u = np.array([oracle.negabinary(int(q[order[c]])) for c in range(16)], dtype=np.uint32)
+        bits, _ = o2.encode_planes(u, budget)
+        want = np.zeros(16 * rate, dtype=np.uint8)
+        want[:8] = [(E >> t) & 1 for t in range(8)]
+        want[8:] = bits[:budget]
+        assert np.array_equal(np.unpackbits(blk, bitorder="little"), want)
+        last_bit_set += int(want[-1])
+        # the decoder: the same stages backwards on exactly those bits
+        ud = o2.decode_planes(want[8:], budget)
+        qd = np.zeros(16, dtype=np.int64)
+        for c in range(16):
+            qd[order[c]] = oracle.inv_negabinary(int(ud[c]))
+        xd = o2.dequantise(o2.inv_transform(qd), E)
+        got = o2.decode_block(blk, rate)
+        assert np.array_equal(got.view(np.uint32), xd.view(np.uint32))
+        flipped = blk.copy()
+        flipped[-1] ^= 0x80
+        last_bit_read += int(not np.array_equal(o2.decode_block(flipped, rate).view(np.uint32), got.view(np.uint32)))
+        # bytes after the block are not the block's business
+        longer = np.concatenate([blk, np.full(4, 0xFF, dtype=np.uint8)])
+        assert np.array_equal(o2.decode_block(longer[:2 * rate], rate).view(np.uint32), got.view(np.uint32))
+    if rate <= 16:   # (at rate 32 the code of a block ends before the budget does)
+        assert last_bit_set > 0 and last_bit_read > 0, (rate, last_bit_set, last_bit_read)
+
+
+def test_ring_hop_calls_take_one_to_sixteen_chunks(o2):
+    ones = np.ones((5, 6), dtype=np.float32)
+    c = o2.compress(ones, 8)
+    local = np.full((5, 6), 0.5, dtype=np.float32)
+    for call in (lambda chunks: o2.reduce_mixed(chunks, local, 5, 6, 8), lambda chunks: o2.reduce_decompress(chunks, local, 5, 6, 8)):
+        with pytest.raises(ValueError):
+            call([])
+        with pytest.raises(ValueError):
+            call([c] * 17)
+    assert np.array_equal(o2.reduce_decompress([c] * 16, local, 5, 6, 8), np.full((5, 6), 16.5, dtype=np.float32))
+    assert np.array_equal(o2.reduce_mixed([c] * 16, local, 5, 6, 8), o2.compress(np.full((5, 6), 16.5, dtype=np.float32), 8))
+    assert np.array_equal(o2.reduce_compressed([c] * 16, 5, 6, 8), o2.compress(np.full((5, 6), 16, dtype=np.float32), 8))

@@ -302,3 +302,64 @@ def test_requantising_chain_error_per_rate(oracle):
     assert hops8[-1] < 6 * hops8[0] and hops8[-1] < 0.3 * std and direct8 < 0.15 * std
     assert all(b > a for a, b in zip(hops8[:-1], hops8[1:]))
     assert rmse[16][0][-1] < 1e-3 * std
+
+
+@pytest.mark.parametrize("n", [1, 5, 4097, 2, 6, 4098, 3, 4099, 4, 4096])
+def test_every_call_on_every_ragged_length(oracle, n):
+    """All buffer calls at lengths with every remainder modulo 4, against their definitions
+    spelled out with numpy: the last block holds n mod 4 values, its pad repeats the last valid
+    value (for the reduce calls: the last valid SUM), and nothing beyond n values is produced."""
+    x = [workloads.gradient_iid(4100, index=40 + j) * np.float32(1 + j) for j in range(3)]
+    local = workloads.gradient_iid(4100, index=50)[:n]
+    blocks = (n + 3) // 4
+    for rate in (4, 16):
+        comp = [oracle.compress(v[:n], rate) for v in x]
+        assert all(c.size == blocks * rate // 2 for c in comp)
+        # the last block of the stream is the block of the padded values
+        tail = np.concatenate([x[0][4 * (blocks - 1):n], np.repeat(x[0][n - 1], 4 * blocks - n)])
+        assert np.array_equal(comp[0][-(rate // 2):], oracle.encode_block(tail, rate))
+        dec = [oracle.decompress(c, n, rate) for c in comp]
+        assert dec[0].size == n
+        assert np.array_equal(dec[0][4 * (blocks - 1):].view(np.uint32),
+                              oracle.decode_block(comp[0][-(rate // 2):], rate)[:n - 4 * (blocks - 1)].view(np.uint32))
+        for k in (1, 3):
+            total = dec[0].copy()
+            for j in range(1, k):
+                total = (total + dec[j]).astype(np.float32)
+            assert np.array_equal(oracle.reduce_compressed(comp[:k], n, rate), oracle.compress(total, rate))
+            assert np.array_equal(oracle.reduce_decompress(comp[:k], None, n, rate).view(np.uint32), total.view(np.uint32))
+            with_local = (total + local).astype(np.float32)
+            assert np.array_equal(oracle.reduce_mixed(comp[:k], local, n, rate), oracle.compress(with_local, rate))
+            assert np.array_equal(oracle.reduce_decompress(comp[:k], local, n, rate).view(np.uint32), with_local.view(np.uint32))
+
+
+def test_what_the_output_buffer_held_before_does_not_matter(oracle):
+    """Every bit of every block is written, zeros included: compressing and reducing into a
+    buffer full of ones gives the same bytes as into a buffer of zeros."""
+    import ctypes
+    L = oracle.lib()
+    n = 4 * 300 + 1
+    x = workloads.gradient_iid(n)
+    y = workloads.gradient_iid(n, index=3)
+    for rate in (4, 8, 12, 24, 32):
+        want = oracle.compress(x, rate)
+        out = np.full(want.size, 0xFF, dtype=np.uint8)
+        assert L.zc_ref_compress(x.ctypes.data, n, rate, out.ctypes.data, out.size) == 0
+        assert np.array_equal(out, want), rate
+        other = oracle.compress(y, rate)
+        ptrs = (ctypes.c_void_p * 2)(want.ctypes.data, other.ctypes.data)
+        out = np.full(want.size, 0xFF, dtype=np.uint8)
+        assert L.zc_ref_reduce_compressed(ptrs, 2, n, rate, out.ctypes.data, out.size) == 0
+        assert np.array_equal(out, oracle.reduce_compressed([want, other], n, rate)), rate
+
+
+def test_ring_hop_calls_take_one_to_sixteen_chunks(oracle):
+    c = oracle.compress(np.ones(9, dtype=np.float32), 8)
+    local = np.full(9, 0.5, dtype=np.float32)
+    for call in (lambda chunks: oracle.reduce_mixed(chunks, local, 9, 8), lambda chunks: oracle.reduce_decompress(chunks, local, 9, 8)):
+        with pytest.raises(ValueError):
+            call([])
+        with pytest.raises(ValueError):
+            call([c] * 17)
+    assert np.array_equal(oracle.reduce_decompress([c] * 16, local, 9, 8), np.full(9, 16.5, dtype=np.float32))
+    assert np.array_equal(oracle.reduce_mixed([c] * 16, local, 9, 8), oracle.compress(np.full(9, 16.5, dtype=np.float32), 8))

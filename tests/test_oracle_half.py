@@ -96,3 +96,12 @@ def test_buffer_calls_are_compositions(oracle):
                     b = d.view(np.uint32).astype(np.uint64)
                     want = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
                 assert np.array_equal(got, want)
+
+
+def test_narrowing_a_nan_gives_the_formats_quiet_nan(oracle):
+    """Not-a-number narrows to one fixed pattern per format, the positive quiet NaN with an empty
+    payload: 0x7FC0 (bf16), 0x7E00 (fp16), whatever the sign and payload of the fp32 NaN."""
+    for bits in (0x7FC00000, 0xFFC00000, 0x7F800001, 0xFFFFFFFF, 0x7FC12345):
+        v = np.array([bits], dtype=np.uint32).view(np.float32)[0]
+        assert oracle.narrow(v, oracle.BF16) == 0x7FC0
+        assert oracle.narrow(v, oracle.F16) == 0x7E00
