@@ -156,6 +156,27 @@ def test_16_bit_messages(gpu, ref, n):
         _same(_host(words).view(np.uint32), h.astype(np.uint32) << np.uint32(16), "16-bit stream as words %s" % name)
 
 
+def test_16_bit_decoder_on_streams_of_full_words(gpu, ref):
+    """A stream whose words use all 32 bits, decoded as a 16-bit message: the decoder's short form
+    (only the upper 16 planes, which is all a stream made from 16-bit words has) does not apply,
+    and the result is the upper halves of the decoded words, as in the reference.  Chunks of both
+    kinds side by side in one stream as well."""
+    import torch
+    n = 6 * C + 77
+    full = workloads.gradient_iid(n, config=1, index=3).view(np.uint32)
+    mixed = full.copy()
+    mixed[C:3 * C] &= np.uint32(0xFFFF0000)          # two chunks that look as if made from 16-bit words
+    for name, w in (("full words", full), ("mixed chunks", mixed)):
+        print("lossless 16-bit decoder,", name, flush=True)
+        stream = ref.compress(w)
+        want = ref.decompress16(stream, n)
+        assert np.array_equal(want, (w >> np.uint32(16)).astype(np.uint16))
+        back = torch.full((n + 32,), -7, dtype=torch.int16, device="cuda")
+        gpu.zl_decompress16(_dev(stream), n, d_out=back[:n])
+        _same(_host(back[:n]).view(np.uint16), want, "16-bit decode of %s" % name)
+        assert (_host(back[n:]) == -7).all()
+
+
 def test_two_compressions_at_once(gpu, ref):
     """Two messages compressed on two streams at the same time (each kernel alone would fill
     the chip): both streams must come out as the reference's, several times over."""
