@@ -24,9 +24,13 @@
 //   * decoder: a table indexed by the next 9 stream bits and by how far the last
 //     coefficient is (whose token has no closing one) decodes all the tokens that lie
 //     whole within those bits; it is used when its result stays inside the budget,
-//     otherwise one token is decoded by count-trailing-zeros with the limits applied.  A budget cut inside
-//     a run places the decoded one after the zeros read so far, which is the lowest
-//     index still possible.
+//     otherwise one token is decoded by count-trailing-zeros with the limits applied.
+//     A budget cut inside a run places the decoded one after the zeros read so far, which
+//     is the lowest index still possible.  A lane's progress through a plane is one state
+//     word that table entries are added to; lanes whose plane is closed read an all-zero
+//     row, so that a step needs no per-lane case distinction;
+//   * after the planes, the usual case (at most 16 planes read, starting within the top
+//     16) turns each coefficient's 16-bit pattern into its word with one shift.
 #ifndef ZC2D_CODEC_H
 #define ZC2D_CODEC_H
 

@@ -4,7 +4,7 @@
 // stride, so that the 64 lanes of a wavefront read four contiguous 1 KiB spans (one per
 // matrix row of the block row) and write one contiguous span of 64 * 2*RATE stream bytes.
 // A block lives in registers from load to store; LDS holds only the coder's look-up table
-// (1 KiB for the encoder, 20 KiB for the decoder).  No matrix cores: nothing here is a
+// (1 KiB for the encoder, 22 KiB for the decoder).  No matrix cores: nothing here is a
 // contraction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
