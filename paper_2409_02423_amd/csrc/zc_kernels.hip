@@ -30,6 +30,9 @@ constexpr int kEnc4Words = (1 << 13) / 4;
 constexpr int kMaxChunks = 16;
 constexpr size_t kWideBlocks = 512;     // blocks per wavefront and pass of the wide rate-4 kernels
 
+// The wavefront-wide votes of the codec: lanes(p) is the set of lanes where p holds (taken
+// per comparison, so that the compare instruction's own mask is the set and sets combine on
+// the scalar side), some(set) whether it is non-empty; any_lane_active(p) = some(lanes(p)).
 struct AnyLane {
   __device__ uint64_t lanes(bool p) const { return __builtin_amdgcn_ballot_w64(p); }
   __device__ bool some(uint64_t set) const { return set != 0; }
