@@ -376,6 +376,13 @@ def main():
                     "algorithmic_GBps": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9, 1),
                     "hbm_frac": frac(algorithmic_bytes(nm, n, rate), avg_ms[nm])}
                for nm in names}
+    # the fused reduce is bound by integer work, not by bytes: its share of the integer ALU peak, from
+    # the instruction count in the tracked profile (absent if that summary has no row for the kernel)
+    reduce_prof = profiled_counters().get(KERNEL_NAMES["reduce"], {})
+    if "valu_wave_insts" in reduce_prof:
+        lane_ops = reduce_prof["valu_wave_insts"] * 64
+        kernels["reduce"]["int_alu_frac"] = round(lane_ops / (avg_ms["reduce"] * 1e-3) / 1e12 / INT_ALU_PEAK_TOPS, 4)
+        kernels["reduce"]["valu_instructions_per_block"] = round(reduce_prof["valu_wave_insts"] * 64 / (n / 4), 1)
 
     result = {
         "metric": "compress/decompress/reduce GB/s (uncompressed fp32) and % of HBM peak",
