@@ -506,10 +506,11 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
           make_word(w);
           made = w + 1;
         }
-        uint32_t z = lit[w], s = 0;
+        uint32_t z = lit[w], togo = 4u;   // steps this word still has bytes for
 #pragma unroll 1
-        for (; s < 4u; ++s) {
-          if (!any_lane_active.some(any_lane_active.lanes(left > 0) & any_lane_active.lanes(state < 3u * 256u * 4u))) break;
+        while (togo != 0u && any_lane_active.some(any_lane_active.lanes(left > 0) & any_lane_active.lanes(state < 3u * 256u * 4u))) {
+          --togo;
+          ++steps;
           uint32_t byte = z & 0xFFu;
           materialise(byte);   // (so that the address is this byte shifted and added to the row's offset in one instruction)
           const uint32_t e = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(tab.enc) + state + (byte << 2));
@@ -519,8 +520,7 @@ ZC_DEV void encode_block(const uint32_t (&x)[4], const Tables& tab, uint32_t (&W
           left -= len;
           state = e >> 18;
         }
-        steps += s;
-        open = s == 4u;
+        open = togo == 0u;
       }
     }
     // word j of the string is needed below iff some lane's budget reaches past bit 32*j of it
