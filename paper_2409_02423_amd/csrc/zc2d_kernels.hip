@@ -31,7 +31,7 @@ __device__ __forceinline__ void stage_table(const uint32_t* __restrict__ src, ui
 }
 // Workgroups per CU in the grid (measured: the decoder-bound kernels like a few more than
 // the compress kernel).  Only a build with -DZC_TUNING_KNOBS lets ZC2D_WORKGROUPS_PER_CU override both; the shipped library reads no environment variable.
-constexpr int kCompressWorkgroupsPerCU = 16, kDecodeWorkgroupsPerCU = 32;
+constexpr int kCompressWorkgroupsPerCU = 16, kDecodeWorkgroupsPerCU = 48;
 
 // The wavefront-wide votes of the codec: lanes(p) is the set of lanes where p holds (one
 // comparison each, so that the compare instruction's own mask is the set), some(set) whether
