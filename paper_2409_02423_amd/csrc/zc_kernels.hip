@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const void* __restri
       for (int u = 0; u < U; ++u) {
         uint32_t W[NW];
         zc::encode_block<RATE>(x[u], tab, W, AnyLane());
-        store_stream<RATE, true>(out, t * kTile + u * kThreads + threadIdx.x, W);
+        store_stream<RATE, (RATE != 12)>(out, t * kTile + u * kThreads + threadIdx.x, W);   // (rate 12, three 2-byte stores per block: plain stores measured 9 % faster)
       }
       if (!more) break;
 #pragma unroll
