@@ -605,7 +605,7 @@ int compute_units() {
 // arithmetic, is flat from 32 to 96 and worse outside.
 // The library reads no environment variable; only a build with -DZC_TUNING_KNOBS (never
 // the shipped one) lets ZC_WORKGROUPS_PER_CU override these numbers for tuning runs.
-enum Kernel { kCompress, kDecompress, kReduce };
+enum Kernel { kCompress, kDecompress, kReduce, kReduceRaw };   // kReduceRaw: the reduce that stores fp32
 
 int workgroups_per_cu(Kernel kernel, int rate) {
 #ifdef ZC_TUNING_KNOBS
@@ -617,6 +617,7 @@ int workgroups_per_cu(Kernel kernel, int rate) {
   switch (kernel) {
     case kCompress: return 128;
     case kDecompress: return rate == 4 || rate >= 16 ? 128 : 112;
+    case kReduceRaw: return rate >= 16 ? 128 : 96;   // writes 16 bytes per block: closer to the decoder than to the reduce
     default: return rate == 4 ? 48 : 64;
   }
 }
@@ -812,7 +813,7 @@ static int launch_reduce(const void* const* d_in, int k, const float* d_local, s
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint8_t* out = static_cast<uint8_t*>(d_out);
 #define LAUNCH_K(R, LOCAL, RAW, K)                                                                            \
-  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW, K>), dim3(grid_for(n, kReduce, R)),    \
+  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW, K>), dim3(grid_for(n, RAW ? kReduceRaw : kReduce, R)),    \
                      dim3(kThreads), 0, s, chunks, k, d_local, n, out, d_out_raw)
 #define LAUNCH(R, LOCAL, RAW)                 \
   do {                                        \
