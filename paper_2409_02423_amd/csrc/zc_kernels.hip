@@ -622,10 +622,18 @@ int workgroups_per_cu(Kernel kernel, int rate) {
   }
 }
 
-unsigned grid_for(size_t n, Kernel kernel, int rate) {
-  size_t blocks = (n + 3) / 4;
-  size_t groups = (blocks + kThreads - 1) / kThreads;
-  size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu(kernel, rate);
+// blocks_per_lane: the kernel's U; a workgroup's unit of work is a tile of U * 256 blocks, and
+// no more workgroups are launched than there are tiles (each stages the code tables first:
+// a workgroup without a tile would do that for nothing), at least `tiles_each` tiles apiece.
+unsigned grid_for(size_t n, Kernel kernel, int rate, int blocks_per_lane) {
+  const size_t blocks = (n + 3) / 4, tile = (size_t)blocks_per_lane * kThreads;
+  size_t tiles_each = 1;
+#ifdef ZC_TUNING_KNOBS
+  if (const char* e = getenv("ZC_TILES_EACH")) tiles_each = (size_t)atoi(e) > 0 ? (size_t)atoi(e) : 1;
+#endif
+  size_t groups = (blocks + tile * tiles_each - 1) / (tile * tiles_each);
+  if (groups == 0) groups = 1;
+  const size_t cap = (size_t)compute_units() * (size_t)workgroups_per_cu(kernel, rate);
   return (unsigned)(groups < cap ? groups : cap);
 }
 
@@ -723,7 +731,7 @@ static int launch_compress(const void* d_in, int dtype, size_t n, int rate, void
     if (n == 0) return finish_launch();
   }
 #define LAUNCH(R, DT)                                                                                            \
-  hipLaunchKernelGGL((compress_kernel<R, compress_unroll<R>(), DT>), dim3(grid_for(n, kCompress, R)),            \
+  hipLaunchKernelGGL((compress_kernel<R, compress_unroll<R>(), DT>), dim3(grid_for(n, kCompress, R, compress_unroll<R>())), \
                      dim3(kThreads), 0, s, d_in, n, out)
 #define CALL(R)                                   \
   do {                                            \
@@ -761,7 +769,7 @@ static int launch_decompress(const void* d_in, size_t n, int rate, int dtype, vo
     if (n == 0) return finish_launch();
   }
 #define LAUNCH(R, DT)                                                                                            \
-  hipLaunchKernelGGL((decompress_kernel<R, decompress_unroll<R>(), DT>), dim3(grid_for(n, kDecompress, R)),      \
+  hipLaunchKernelGGL((decompress_kernel<R, decompress_unroll<R>(), DT>), dim3(grid_for(n, kDecompress, R, decompress_unroll<R>())), \
                      dim3(kThreads), 0, s, in, n, d_out)
 #define CALL(R)                                   \
   do {                                            \
@@ -813,7 +821,7 @@ static int launch_reduce(const void* const* d_in, int k, const float* d_local, s
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint8_t* out = static_cast<uint8_t*>(d_out);
 #define LAUNCH_K(R, LOCAL, RAW, K)                                                                            \
-  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW, K>), dim3(grid_for(n, RAW ? kReduceRaw : kReduce, R)),    \
+  hipLaunchKernelGGL((reduce_kernel<R, reduce_unroll<R>(), LOCAL, RAW, K>), dim3(grid_for(n, RAW ? kReduceRaw : kReduce, R, reduce_unroll<R>())),    \
                      dim3(kThreads), 0, s, chunks, k, d_local, n, out, d_out_raw)
 #define LAUNCH(R, LOCAL, RAW)                 \
   do {                                        \
