@@ -21,12 +21,31 @@ constexpr int kThreads = 256;
 __device__ __align__(16) const zc2d::ExpandTable g_expand = zc2d::build_expand_table();
 __device__ __align__(16) const zc2d::TokenTable g_token = zc2d::build_token_table();
 
-// Copy a table of WORDS 32-bit words to LDS, 16 bytes per lane and step.
+// Copy a table of WORDS 32-bit words to LDS, 16 bytes per lane and step: a lane issues all of
+// its loads back to back and then writes (one wait for the whole table, not one per step).
+// In a last, partial step of several the lanes beyond the table's end copy its first entry
+// once more.
 template <int WORDS>
 __device__ __forceinline__ void stage_table(const uint32_t* __restrict__ src, uint32_t* dst) {
   static_assert(WORDS % 4 == 0, "table size");
-  for (int i = threadIdx.x; i < WORDS / 4; i += kThreads)
-    reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(src)[i];
+  constexpr int kVecs = WORDS / 4;
+  constexpr int kSteps = (kVecs + kThreads - 1) / kThreads;
+  if constexpr (kSteps == 1) {
+    if (threadIdx.x < kVecs) reinterpret_cast<uint4*>(dst)[threadIdx.x] = reinterpret_cast<const uint4*>(src)[threadIdx.x];
+  } else {
+    uint4 v[kSteps];
+    int idx[kSteps];
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+      idx[i] = threadIdx.x + i * kThreads;
+      if ((i + 1) * kThreads > kVecs && idx[i] >= kVecs) idx[i] = 0;
+      v[i] = reinterpret_cast<const uint4*>(src)[idx[i]];
+    }
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) reinterpret_cast<uint4*>(dst)[idx[i]] = v[i];
+    __builtin_amdgcn_sched_group_barrier(0x020, kSteps, 0);   // (for the instruction scheduler: the loads first,
+    __builtin_amdgcn_sched_group_barrier(0x200, kSteps, 0);   // then the LDS writes)
+  }
   __syncthreads();
 }
 // Workgroups per CU in the grid (measured: the decoder-bound kernels like a few more than

@@ -39,7 +39,7 @@ struct AnyLane {
   __device__ bool operator()(bool p) const { return __builtin_amdgcn_ballot_w64(p) != 0; }
 };
 
-// Copy a code table into LDS: every thread issues all of its 16-byte loads back to back.
+// Copy a code table into LDS, 16 bytes per lane and step.
 template <int WORDS>
 __device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table) {
   static_assert(WORDS % 4 == 0, "table size");
@@ -58,41 +58,91 @@ __device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table
   }
 }
 
+// The same in two parts, for the fused reduce, which needs two tables: every lane issues all
+// of its loads of both back to back before it writes, one wait instead of one per step (as
+// the compiler schedules the function above).  That made the reduce kernels 1 to 3 % faster
+// and the decompress kernels, which live on memory rate, 2 to 3 % slower, so only the former
+// use it.  In a last, partial step the lanes beyond the table's end copy its first entry once more.
+template <int WORDS>
+struct TableCopy {
+  static_assert(WORDS % 4 == 0, "table size");
+  static constexpr int kVecs = WORDS / 4;
+  static constexpr int kSteps = (kVecs + kThreads - 1) / kThreads;
+  uint4 v[kSteps];
+  int idx[kSteps];
+  __device__ __forceinline__ explicit TableCopy(const uint32_t* table) {
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+      idx[i] = threadIdx.x + i * kThreads;
+      if ((i + 1) * kThreads > kVecs && idx[i] >= kVecs) idx[i] = 0;
+      v[i] = reinterpret_cast<const uint4*>(table)[idx[i]];
+    }
+  }
+  __device__ __forceinline__ void put(uint32_t* lds) const {
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) reinterpret_cast<uint4*>(lds)[idx[i]] = v[i];
+  }
+};
+
 // Rate 4 encodes its one payload byte with one look-up in the 8192-entry table; the other
 // rates use the two-planes-per-step table.
 template <int RATE>
 constexpr int encoder_table_words() { return RATE == 4 ? kEnc4Words : kEncWords; }
-
 template <int RATE>
-__device__ __forceinline__ void stage_encoder_table(uint32_t* lds) {
-  if constexpr (RATE == 4) stage_table<kEnc4Words>(lds, reinterpret_cast<const uint32_t*>(g_enc4_table.v));
-  else stage_table<kEncWords>(lds, g_enc_table.v);
+__device__ __forceinline__ const uint32_t* encoder_table() {
+  if constexpr (RATE == 4) return reinterpret_cast<const uint32_t*>(g_enc4_table.v);
+  else return g_enc_table.v;
 }
 
 // Rate 4 decodes its one payload byte with the 256-entry block table; the other rates
 // use the per-plane table.
 template <int RATE>
 constexpr int decoder_table_words() { return RATE == 4 ? kDec4Words : kDecWords; }
+template <int RATE>
+__device__ __forceinline__ const uint32_t* decoder_table() {
+  if constexpr (RATE == 4) return reinterpret_cast<const uint32_t*>(g_dec4_table.v);
+  else return g_dec_table.v;
+}
+
+template <int RATE>
+__device__ __forceinline__ zc::Tables decoder_tables(const uint32_t* dec, const uint32_t* enc) {
+  if constexpr (RATE == 4) return zc::Tables{enc, nullptr, reinterpret_cast<const float*>(dec)};
+  else return zc::Tables{enc, dec, nullptr};
+}
+
+template <int RATE>
+__device__ __forceinline__ void stage_encoder_table(uint32_t* lds) {
+  stage_table<encoder_table_words<RATE>()>(lds, encoder_table<RATE>());
+}
 
 template <int RATE>
 __device__ __forceinline__ zc::Tables stage_decoder_table(uint32_t* lds, const uint32_t* enc) {
-  if constexpr (RATE == 4) {
-    stage_table<kDec4Words>(lds, reinterpret_cast<const uint32_t*>(g_dec4_table.v));
-    return zc::Tables{enc, nullptr, reinterpret_cast<const float*>(lds)};
-  } else {
-    stage_table<kDecWords>(lds, g_dec_table.v);
-    return zc::Tables{enc, lds, nullptr};
-  }
+  stage_table<decoder_table_words<RATE>()>(lds, decoder_table<RATE>());
+  return decoder_tables<RATE>(lds, enc);
+}
+
+// Both tables (the fused reduce with a compressed output).
+template <int RATE>
+__device__ __forceinline__ zc::Tables stage_coder_tables(uint32_t* dec, uint32_t* enc) {
+  using Dec = TableCopy<decoder_table_words<RATE>()>;
+  using Enc = TableCopy<encoder_table_words<RATE>()>;
+  const Dec d(decoder_table<RATE>());
+  const Enc e(encoder_table<RATE>());
+  d.put(dec);
+  e.put(enc);
+  __builtin_amdgcn_sched_group_barrier(0x020, Dec::kSteps + Enc::kSteps, 0);   // (for the instruction scheduler: the loads first,
+  __builtin_amdgcn_sched_group_barrier(0x200, Dec::kSteps + Enc::kSteps, 0);   // then the LDS writes)
+  return decoder_tables<RATE>(dec, enc);
 }
 
 // ---- block I/O ----------------------------------------------------------------------
 
 // Message buffers are streamed once.  Measured on MI355X: non-temporal 16-byte fp32
 // loads and stores are faster than plain ones (the decompress kernel's 1 GiB of
-// output by a third); for the narrow compressed stream, non-temporal loads are slower
-// than plain ones, and plain stores let the kernel that consumes the stream next find
-// part of it in the last-level cache.  So fp32 in and out are non-temporal, stream in
-// and out are plain.
+// output by a third).  The narrow compressed stream is read with non-temporal loads as well
+// (see load_stream; the rate-4 decompress kernel that takes 16 bytes per lane uses a plain
+// load) and written with non-temporal stores by the compress kernels and plain ones by the
+// fused reduce (see store_stream).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -444,8 +494,9 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
   const int k = K > 0 ? K : k_given;   // K > 0: the number of chunks is known when the kernel is compiled
   __shared__ __align__(16) uint32_t dec[decoder_table_words<RATE>()];
   __shared__ __align__(16) uint32_t enc[RAW_OUT ? 4 : encoder_table_words<RATE>()];
-  if constexpr (!RAW_OUT) stage_encoder_table<RATE>(enc);
-  const zc::Tables tab = stage_decoder_table<RATE>(dec, enc);
+  zc::Tables tab;
+  if constexpr (RAW_OUT) tab = stage_decoder_table<RATE>(dec, enc);
+  else tab = stage_coder_tables<RATE>(dec, enc);
   __syncthreads();
   constexpr int NW = zc::Traits<RATE>::kWords;
   constexpr size_t kTile = (size_t)U * kThreads;
