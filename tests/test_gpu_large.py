@@ -34,6 +34,8 @@ def test_one_dimensional_beyond_2_to_32(oracle):
         assert c.numel() == zc.zc_compressed_size(n, rate) == ((n + 3) // 4) * bb
         y = zc.zc_decompress(c, n, rate)
         r = zc.zc_reduce_compressed([c, c], n, rate)
+        hop = zc.zc_reduce_mixed([c], x, n, rate)               # the ring-hop calls: stream(s) plus raw local values
+        last = zc.zc_reduce_decompress([c, c], x, n, rate)
         blocks = (n + 3) // 4
         for b0, count in ((0, 4096), ((1 << 30) - 2048, 4096), (blocks - 4096, 4096)):
             print("large 1-D rate", rate, "blocks from", b0, flush=True)
@@ -43,7 +45,10 @@ def test_one_dimensional_beyond_2_to_32(oracle):
             assert np.array_equal(_host(c[b0 * bb:(b0 + count) * bb]), want), (rate, b0)
             assert np.array_equal(_host(y[lo:hi]).view(np.uint32), oracle.decompress(want, xs.size, rate).view(np.uint32))
             assert np.array_equal(_host(r[b0 * bb:(b0 + count) * bb]), oracle.reduce_compressed([want, want], xs.size, rate))
-        del c, y, r
+            assert np.array_equal(_host(hop[b0 * bb:(b0 + count) * bb]), oracle.reduce_mixed([want], xs, xs.size, rate))
+            assert np.array_equal(_host(last[lo:hi]).view(np.uint32),
+                                  oracle.reduce_decompress([want, want], xs, xs.size, rate).view(np.uint32))
+        del c, y, r, hop, last
     del x
     torch.cuda.empty_cache()
 
