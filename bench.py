@@ -370,7 +370,8 @@ def main():
                      "frac_of_measured_copy": round(achieved / copy_gbps, 4) if roofline["bound"] == "hbm" else None,
                      "stream_input": "the 128 MiB stream the decompress kernel reads was written by the reduce kernel just "
                                      "before it with plain stores, so part of it may come from the 256 MB last-level cache "
-                                     "(at most 11 % of the kernel's bytes); the fp32 side is 1 GiB and comes from / goes to HBM"})
+                                     "(at most 11 % of the kernel's bytes); the fp32 side is 1 GiB and comes from / goes to HBM; "
+                                     "`decompress_from_hbm` has the same kernel alone on streams that lie in HBM"})
     kernels = {nm: {"avg_ms": round(avg_ms[nm], 4),
                     "uncompressed_GBps": round(4 * n / (avg_ms[nm] * 1e-3) / 1e9, 1),
                     "algorithmic_GBps": round(algorithmic_bytes(nm, n, rate) / (avg_ms[nm] * 1e-3) / 1e9, 1),
