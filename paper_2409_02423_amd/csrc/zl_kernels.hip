@@ -394,15 +394,31 @@ __global__ __launch_bounds__(kThreads) void zl_decompress_kernel(const uint8_t* 
   const uint64_t held = words > 2 * kThreads ? words - 2 * kThreads : 0;
   const uint32_t stored = held < (uint64_t)zl::kChunkWords ? (uint32_t)held : (uint32_t)zl::kChunkWords;
   src += 2 * kThreads;
+  // (a chunk that holds 16 planes per group or fewer, as every chunk of a 16-bit message does,
+  // needs the first half of these loads and of the staging only; what a malformed stream then
+  // picks up beyond its span is whatever the staging area held, which is as unspecified as
+  // zeros would be)
+  const bool upper_half = stored > 16u * kThreads;
   uint32_t p[32];
 #pragma unroll
-  for (int q = 0; q < 32; ++q) {
+  for (int q = 0; q < 16; ++q) {
     const uint32_t i = tid + kThreads * q;
     p[q] = i < stored ? src[i] : 0u;
   }
+  if (upper_half) {
+#pragma unroll
+    for (int q = 16; q < 32; ++q) {
+      const uint32_t i = tid + kThreads * q;
+      p[q] = i < stored ? src[i] : 0u;
+    }
+  }
   const Places at = workgroup_places((uint32_t)__builtin_popcount(bitmap), wave_totals);
 #pragma unroll
-  for (int q = 0; q < 32; ++q) stage[staged(tid + kThreads * q)] = p[q];
+  for (int q = 0; q < 16; ++q) stage[staged(tid + kThreads * q)] = p[q];
+  if (upper_half) {
+#pragma unroll
+    for (int q = 16; q < 32; ++q) stage[staged(tid + kThreads * q)] = p[q];
+  }
   __syncthreads();
   uint32_t pos = at.wave_start + at.in_wave;
   if constexpr (HALF) {
