@@ -398,14 +398,22 @@ __global__ __launch_bounds__(kThreads) void compress4_wide_kernel(const void* __
   __syncthreads();
   const zc::Tables tab = {enc, nullptr, nullptr};
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const size_t stride = (size_t)gridDim.x * (kThreads / 64);
-  size_t t = (size_t)blockIdx.x * (kThreads / 64) + wave;
+  // a workgroup's four wave tiles are neighbours (32 KiB of fp32 input); these groups of four
+  // are taken in region order, 1 MiB of input per region, as in the decompress kernel below
+  // (a kernel without arithmetic that reads and writes the same way: 0.1945 ms in plain order,
+  // 0.188 ms with regions of 1 or 2 MiB)
+  constexpr int kRegionLg = 5;
+  const size_t groups = wave_tiles / (kThreads / 64), bulk = zc::region_bulk(groups, kRegionLg);
+  auto wave_tile = [&](size_t g) { return g < groups ? zc::region_order(g, bulk, kRegionLg) * (kThreads / 64) + wave : g * (kThreads / 64) + wave; };
+  size_t g = blockIdx.x;
+  size_t t = wave_tile(g);
   if (t >= wave_tiles) return;
   uint32_t x[8][4];
 #pragma unroll
   for (int r = 0; r < 8; ++r) load_values<DT>(in, t * 512 + 64 * r + lane, x[r]);
   for (;;) {
-    const size_t tn = t + stride;
+    const size_t gn = g + gridDim.x;
+    const size_t tn = wave_tile(gn);
     const bool more = tn < wave_tiles;
     const size_t next = (more ? tn : t) * 512 + lane;
     uint32_t xn[8][4];
@@ -428,6 +436,7 @@ __global__ __launch_bounds__(kThreads) void compress4_wide_kernel(const void* __
 #pragma unroll
       for (int i = 0; i < 4; ++i) x[r][i] = xn[r][i];
     t = tn;
+    g = gn;
   }
 }
 
