@@ -333,11 +333,34 @@ constexpr Dec4Table build_dec4_table() {
   return t;
 }
 
+// The same entries as IEEE half-precision bit patterns (integers below 2^9 are exact in a
+// half's 11 significant bits), 8 bytes per payload value: the fused reduce reads these for
+// every chunk after the first and feeds them to its multiply-add as they are (the GPU has a
+// multiply-add that widens a half operand on the way in), which halves the LDS traffic of a
+// look-up.
+struct Dec4HalfTable { uint16_t v[256 * 4]; };
+
+constexpr uint16_t small_int_as_half(int32_t x) {   // |x| < 2048
+  if (x == 0) return 0;
+  const uint32_t sign = x < 0 ? 0x8000u : 0u, m = (uint32_t)(x < 0 ? -x : x);
+  int e = 0;
+  while ((m >> (e + 1)) != 0) ++e;   // the exponent of the leading one, at most 10
+  return (uint16_t)(sign | (uint32_t)(15 + e) << 10 | ((m << (10 - e)) & 0x3FFu));
+}
+
+constexpr Dec4HalfTable build_dec4_half_table() {
+  const Dec4Table f = build_dec4_table();
+  Dec4HalfTable t{};
+  for (int i = 0; i < 256 * 4; ++i) t.v[i] = small_int_as_half((int32_t)f.v[i]);
+  return t;
+}
+
 // Pointers to the staged tables; a kernel sets only those its rate uses.
 struct Tables {
   const uint32_t* enc;   // EncTable; at rate 4 the bytes of Enc4Table
   const uint32_t* dec;
   const float* dec4;
+  const uint16_t* dec4_half;   // Dec4HalfTable (the fused reduce at rate 4)
 };
 
 template <int V>
@@ -755,15 +778,37 @@ ZC_DEV void decode_block(uint32_t (&W)[Traits<RATE>::kWords], const Tables& tab,
 // is four zeros, so a zero block with a zero payload needs no test of its exponent byte.
 template <bool FIRST>
 ZC_DEV void accumulate_plain4(uint32_t W0, const Tables& tab, float (&sum)[4]) {
-  const float* q = reinterpret_cast<const float*>(reinterpret_cast<const char*>(tab.dec4) + (((W0 >> 8) & 0xFFu) << 4));
   const int ex = (int)(W0 & 0xFFu) - 127 - kFractionBits + 22;
   if constexpr (FIRST) {
+    const float* q = reinterpret_cast<const float*>(reinterpret_cast<const char*>(tab.dec4) + (((W0 >> 8) & 0xFFu) << 4));
 #pragma unroll
     for (int i = 0; i < 4; ++i) sum[i] = __builtin_ldexpf(q[i], ex);
   } else {
     const float scale = __builtin_ldexpf(1.0f, ex);
+    const char* entry = reinterpret_cast<const char*>(tab.dec4_half) + (((W0 >> 8) & 0xFFu) << 3);
+#ifdef __HIP_DEVICE_COMPILE__
+    // eight bytes, four halves; widening a half is exact, so each line is the same fused
+    // multiply-add as on the float entry (one instruction: the half is widened inside it)
+    typedef _Float16 HalfPair __attribute__((ext_vector_type(2)));
+    typedef uint32_t WordPair __attribute__((ext_vector_type(2)));
+    const WordPair raw = *reinterpret_cast<const WordPair*>(entry);
+    // (the two words go through scalars of their own: a bit cast applied to a vector's
+    // component directly took the first component both times with this compiler)
+    const uint32_t first = raw.x, second = raw.y;
+    const HalfPair lo = __builtin_bit_cast(HalfPair, first), hi = __builtin_bit_cast(HalfPair, second);
+    sum[0] = __builtin_fmaf((float)lo.x, scale, sum[0]);
+    sum[1] = __builtin_fmaf((float)lo.y, scale, sum[1]);
+    sum[2] = __builtin_fmaf((float)hi.x, scale, sum[2]);
+    sum[3] = __builtin_fmaf((float)hi.y, scale, sum[3]);
+#else
+    const uint16_t* h = reinterpret_cast<const uint16_t*>(entry);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sum[i] = __builtin_fmaf(q[i], scale, sum[i]);
+    for (int i = 0; i < 4; ++i) {
+      // a normal half or zero: (1 + fraction / 1024) * 2^(exponent - 15)
+      const float q = h[i] & 0x7FFFu ? __builtin_ldexpf((float)(1024 + (h[i] & 0x3FFu)), (int)((h[i] >> 10) & 31u) - 25) : 0.0f;
+      sum[i] = __builtin_fmaf(h[i] & 0x8000u ? -q : q, scale, sum[i]);
+    }
+#endif
   }
 }
 

@@ -14,8 +14,9 @@ const zc::EncTable kEnc = zc::build_enc_table();
 const zc::DecTable kDec = zc::build_dec_table();
 const zc::Dec4Table kDec4 = zc::build_dec4_table();
 alignas(4) const zc::Enc4Table kEnc4 = zc::build_enc4_table();
-const zc::Tables kTables = {kEnc.v, kDec.v, kDec4.v};
-const zc::Tables kTables4 = {reinterpret_cast<const uint32_t*>(kEnc4.v), kDec.v, kDec4.v};
+const zc::Dec4HalfTable kDec4Half = zc::build_dec4_half_table();
+const zc::Tables kTables = {kEnc.v, kDec.v, kDec4.v, kDec4Half.v};
+const zc::Tables kTables4 = {reinterpret_cast<const uint32_t*>(kEnc4.v), kDec.v, kDec4.v, kDec4Half.v};
 // one lane alone: the set of lanes where p holds is p itself
 struct Alone {
   bool lanes(bool p) const { return p; }
