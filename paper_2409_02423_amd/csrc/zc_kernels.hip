@@ -60,8 +60,8 @@ __device__ __forceinline__ void stage_table(uint32_t* lds, const uint32_t* table
   }
 }
 
-// The same in two parts, for the fused reduce, which needs two tables: every lane issues all
-// of its loads of both back to back before it writes, one wait instead of one per step (as
+// The same in two parts, for the fused reduce, which needs two or three tables: every lane issues
+// all of its loads of all of them back to back before it writes, one wait instead of one per step (as
 // the compiler schedules the function above).  That made the reduce kernels 1 to 3 % faster
 // and the decompress kernels, which live on memory rate, 2 to 3 % slower, so only the former
 // use it.  In a last, partial step the lanes beyond the table's end copy its first entry once more.
