@@ -567,7 +567,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
               if constexpr (RATE == 4) {
-                unusual = unusual || zc::unusual4(W[g][u][0]);
+                unusual = unusual | zc::unusual4(W[g][u][0]);
                 if (first) zc::accumulate_plain4<true>(W[g][u][0], tab, s[u]);
                 else zc::accumulate_plain4<false>(W[g][u][0], tab, s[u]);
               } else {
@@ -626,7 +626,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(ChunkPointers chunks, 
           // what that form covers (the tile is then summed again, see below)
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            unusual = unusual || zc::unusual4(W[u][0]);
+            unusual = unusual | zc::unusual4(W[u][0]);
             if (c == 0) zc::accumulate_plain4<true>(W[u][0], tab, s[u]);
             else zc::accumulate_plain4<false>(W[u][0], tab, s[u]);
           }
