@@ -205,10 +205,10 @@ def test_runs_on_a_side_stream(gpu, oracle):
 @pytest.mark.parametrize("rate", MAIN_RATES + (12, 32))
 def test_reduce_matches_reference(gpu, oracle, rate):
     n = 4 * 3000 + 2
-    peers = [workloads.gradient_lowrank(50, 240, tail=2, config=5, index=p) for p in range(8)]
+    peers = [workloads.gradient_lowrank(50, 240, tail=2, config=5, index=p) for p in range(13)]
     comp = [oracle.compress(p, rate) for p in peers]
     dcomp = [_dev(c) for c in comp]
-    for k in (1, 2, 3, 8):
+    for k in (1, 2, 3, 5, 8, 13):   # (the kernel takes the chunks of a tile in groups of four or eight)
         print("reduce rate", rate, "k", k, flush=True)
         want = oracle.reduce_compressed(comp[:k], n, rate)
         got = gpu.zc_reduce_compressed(dcomp[:k], n, rate)
