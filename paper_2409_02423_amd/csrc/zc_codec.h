@@ -355,6 +355,28 @@ constexpr Dec4HalfTable build_dec4_half_table() {
   return t;
 }
 
+namespace selfcheck {
+// every half-precision entry, widened by the format's definition, is the float entry
+constexpr bool dec4_half_ok() {
+  const Dec4Table f = build_dec4_table();
+  const Dec4HalfTable h = build_dec4_half_table();
+  for (int i = 0; i < 256 * 4; ++i) {
+    const uint32_t b = h.v[i];
+    int32_t v = 0;
+    if (b & 0x7FFFu) {
+      const int e = (int)((b >> 10) & 31u) - 15;          // 0 .. 10 for these entries
+      if (e < 0 || e > 10) return false;
+      const uint32_t m = 1024u + (b & 0x3FFu);            // 11 significant bits, worth m * 2^(e - 10)
+      if ((m & ((1u << (10 - e)) - 1u)) != 0) return false;
+      v = (int32_t)(m >> (10 - e));
+    }
+    if ((float)(b & 0x8000u ? -v : v) != f.v[i]) return false;
+  }
+  return true;
+}
+static_assert(dec4_half_ok(), "half-precision copy of the rate-4 block table");
+}  // namespace selfcheck
+
 // Pointers to the staged tables; a kernel sets only those its rate uses.
 struct Tables {
   const uint32_t* enc;   // EncTable; at rate 4 the bytes of Enc4Table
